@@ -1,0 +1,158 @@
+/*
+ * caote.h -- C ABI of the MI355X (gfx950) CAOTE hot path: score cached KV tokens
+ * by the attention-output error of evicting them, keep the top-`budget` per KV
+ * head, and compact the cache in place.
+ *
+ * Method: "CAOTE: KV Cache Selection for LLMs via Attention Output Error-Based
+ * Token Eviction" (arXiv 2504.14051).  Section / equation references below are to
+ * that paper.
+ *
+ * Conventions
+ *   - Every data pointer is DEVICE memory owned by the caller.  `caote_layout*` is
+ *     HOST memory and is read during the call only.
+ *   - The library allocates nothing, keeps no state between calls, and never
+ *     synchronises: all kernels are enqueued on `hip_stream` (a hipStream_t passed
+ *     as void*, NULL = the default stream) and the call returns immediately.
+ *   - Scratch memory comes from the caller: `workspace` must hold at least
+ *     caote_workspace_bytes() bytes, be 256-byte aligned, and must not be shared by
+ *     calls that can overlap in time.
+ *   - Errors: every entry point returns a caote_status.  Argument errors are found
+ *     on the host before anything is launched; a failed launch returns
+ *     CAOTE_EDEVICE.  Nothing aborts or throws.  caote_last_error() gives the text
+ *     of the calling thread's last failure.
+ *   - Token counts: a sequence b holds N_b = seq_lens[b] tokens (or `capacity` when
+ *     seq_lens is NULL).  The caller guarantees window <= N_b <= capacity when
+ *     window_in_cache is set (1 <= N_b otherwise); values of seq_lens outside
+ *     [0, capacity] are clamped on the device, so no access leaves the buffers.
+ *
+ * Shapes (row-major, innermost dimension contiguous, strides in ELEMENTS)
+ *   q_window  [batch][n_q_heads][window][head_dim]     dtype   (strides q_stride_*)
+ *   K, V      [batch][n_kv_heads][capacity][head_dim]  dtype   (strides k_/v_stride_*)
+ *   base_score, scores  [batch][n_kv_heads][capacity]  fp32, dense
+ *   kept_idx  [batch][n_kv_heads][budget]              int32, dense
+ *   Query head hq belongs to KV head hq / (n_q_heads / n_kv_heads).
+ */
+#ifndef CAOTE_H
+#define CAOTE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CAOTE_OK = 0,
+  CAOTE_EINVAL = -1,       /* bad argument (null pointer, inconsistent shape, ...)   */
+  CAOTE_EUNSUPPORTED = -2, /* valid request that the kernels do not cover            */
+  CAOTE_EWORKSPACE = -3,   /* workspace missing, misaligned or too small             */
+  CAOTE_EDEVICE = -4       /* a HIP call failed                                      */
+} caote_status;
+
+typedef enum { CAOTE_BF16 = 0, CAOTE_F32 = 1 } caote_dtype;
+
+/* Base retention score h fed to the CAOTE formula (Sec. 3.2).  a_j is the
+ * attention mass of cached token j summed over all window query rows of the
+ * KV head's group (Sec. 2, f_score,j = sum_i A_ij).                                 */
+typedef enum {
+  CAOTE_BASE_NONE = 0,   /* h = a.  With window = 1 and one query head per KV head
+                            this is TOVA's last-row score (Sec. 2).                 */
+  CAOTE_BASE_H2O = 1,    /* h = base_score + a, written back to base_score: the
+                            accumulated attention of H2O (Sec. 3.2, App. C.1).      */
+  CAOTE_BASE_SNAPKV = 2  /* h = 1-D max-pool (width pool_kernel, stride 1, window
+                            clipped at the ends of the scored range) of a.          */
+} caote_base;
+
+typedef enum {
+  CAOTE_EXACT = 0, /* o = sum_j w_j v_j                       (Sec. 3.2, general score) */
+  CAOTE_FAST = 1   /* o = plain mean of the scored values     (Sec. 3.3, FastCAOTE)     */
+} caote_variant;
+
+typedef enum {
+  CAOTE_COMPACT_STABLE = 0,   /* row i <- row kept_idx[i]; ascending order preserved */
+  CAOTE_COMPACT_SWAP_LAST = 1 /* exactly one token evicted: the last row moves into
+                                 the hole, all other rows stay where they are        */
+} caote_compact_mode;
+
+typedef struct caote_layout {
+  int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim in {64, 128}           */
+  int32_t window;            /* W >= 1: query positions per head in q_window          */
+  int32_t capacity;          /* rows allocated per (sequence, KV head)                */
+  const int32_t* seq_lens;   /* DEVICE [batch] or NULL (every sequence = capacity)    */
+  int64_t k_stride_b, k_stride_h, k_stride_n;
+  int64_t v_stride_b, v_stride_h, v_stride_n;
+  int64_t q_stride_b, q_stride_h, q_stride_w;     /* all multiples of 16 bytes        */
+  int32_t dtype;             /* caote_dtype of q_window, K, V                         */
+  int32_t base;              /* caote_base                                            */
+  float   softmax_scale;     /* multiplies every logit; the paper leaves out the
+                                usual 1/sqrt(head_dim), the caller supplies it        */
+  int32_t pool_kernel;       /* odd, >= 1; used by CAOTE_BASE_SNAPKV only             */
+  int32_t window_in_cache;   /* 1: the last W rows of K/V are the window's own
+                                tokens and attention inside the window is causal
+                                (block-wise prefill, Sec. 2); 0: every key visible    */
+  int32_t n_protect_head;    /* first rows are never evicted                          */
+  int32_t n_protect_tail;    /* last rows are never evicted (SnapKV: the window)      */
+  int32_t variant;           /* caote_variant                                         */
+} caote_layout;
+
+/* Bytes of workspace that any entry point may need for this layout and budget.
+ * Returns 0 if the layout is invalid (see caote_last_error).                        */
+size_t caote_workspace_bytes(const caote_layout* layout, int32_t budget);
+
+/* Scores (Sec. 3.1 CAOTE score; Sec. 3.2 general form; Sec. 3.3 FastCAOTE).
+ * For each sequence and KV head:
+ *   A   = softmax(softmax_scale * Q_window K^T) over the visible keys (Sec. 2),
+ *   a_j = sum over the group's query rows of A_rj,  h from a per `base`,
+ *   scored set S = rows [n_protect_head, N - n_protect_tail),
+ *   w_j = h_j / sum_{S} h,   o = sum_{S} w_j v_j  (or the mean of v over S),
+ *   scores[j] = w_j / (1 - w_j) * || v_j - o ||_2   for j in S,
+ *   scores[j] = +INF for protected rows (and when S has a single token).
+ * Rows at or beyond N_b are not written.
+ *   base_score  in/out for CAOTE_BASE_H2O (all N_b rows are updated); otherwise
+ *               unused and may be NULL.
+ *   scores      out.                                                               */
+caote_status caote_score(const void* q_window, const void* K, const void* V,
+                         float* base_score, const caote_layout* layout,
+                         float* scores, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/* Selection (Sec. 2: the top-b tokens by score are retained).  For each
+ * (sequence, KV head) writes the indices of the `budget` highest scores among
+ * rows [0, N_b) in ASCENDING index order; among equal scores the lower index is
+ * kept.  If N_b <= budget all rows are kept and the tail of the list is -1.
+ * NaN scores are not allowed.                                                      */
+caote_status caote_select(const float* scores, const caote_layout* layout,
+                          int32_t budget, int32_t* kept_idx, void* workspace,
+                          size_t workspace_bytes, void* hip_stream);
+
+/* Cache update (Sec. 2: after eviction attention uses rows i_1..i_b only).
+ * Moves the kept rows of K, V and (if not NULL) base_score to the front of each
+ * (sequence, KV head) slab, in place.  kept_idx must be what caote_select
+ * produced (ascending, unique, -1 padded).  The new length of a sequence is
+ * min(N_b, budget); the caller updates its own seq_lens.  Rows beyond the new
+ * length hold unspecified data afterwards.                                         */
+caote_status caote_compact(void* K, void* V, float* base_score,
+                           const int32_t* kept_idx, const caote_layout* layout,
+                           int32_t budget, int32_t mode, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+/* caote_score + caote_select + caote_compact in one stream-ordered call, with the
+ * same results as the three calls in sequence.  `scores` and `kept_idx` are
+ * outputs as above.                                                                */
+caote_status caote_evict(const void* q_window, void* K, void* V, float* base_score,
+                         const caote_layout* layout, int32_t budget, int32_t mode,
+                         float* scores, int32_t* kept_idx, void* workspace,
+                         size_t workspace_bytes, void* hip_stream);
+
+/* Text of the calling thread's most recent failure ("" if none).  The pointer
+ * stays valid until that thread's next failing call.                               */
+const char* caote_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch.                                */
+int32_t caote_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAOTE_H */

@@ -1,0 +1,170 @@
+"""ctypes binding of the C ABI in ``include/caote.h``.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libcaote_hip.so``.  torch tensors are used as device memory (``data_ptr()``) and for
+the current HIP stream; nothing here computes.  If the library has not been built the
+calls raise -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcaote_hip.so")
+
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EDEVICE = 0, -1, -2, -3, -4
+BF16, F32 = 0, 1
+BASE_NONE, BASE_H2O, BASE_SNAPKV = 0, 1, 2
+EXACT, FAST = 0, 1
+COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
+
+EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
+           "caote_evict", "caote_last_error", "caote_version")
+
+
+class CaoteError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"caote status {status}: {message}")
+        self.status = status
+
+
+class Layout(ctypes.Structure):
+    """Mirror of ``struct caote_layout``."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("window", ctypes.c_int32), ("capacity", ctypes.c_int32),
+        ("seq_lens", ctypes.c_void_p),
+        ("k_stride_b", ctypes.c_int64), ("k_stride_h", ctypes.c_int64), ("k_stride_n", ctypes.c_int64),
+        ("v_stride_b", ctypes.c_int64), ("v_stride_h", ctypes.c_int64), ("v_stride_n", ctypes.c_int64),
+        ("q_stride_b", ctypes.c_int64), ("q_stride_h", ctypes.c_int64), ("q_stride_w", ctypes.c_int64),
+        ("dtype", ctypes.c_int32), ("base", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+        ("pool_kernel", ctypes.c_int32), ("window_in_cache", ctypes.c_int32),
+        ("n_protect_head", ctypes.c_int32), ("n_protect_tail", ctypes.c_int32),
+        ("variant", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2504_14051_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        lp = ctypes.POINTER(Layout)
+        L.caote_workspace_bytes.argtypes = [lp, i32]
+        L.caote_workspace_bytes.restype = sz
+        L.caote_score.argtypes = [vp, vp, vp, vp, lp, vp, vp, sz, vp]
+        L.caote_score.restype = ctypes.c_int
+        L.caote_select.argtypes = [vp, lp, i32, vp, vp, sz, vp]
+        L.caote_select.restype = ctypes.c_int
+        L.caote_compact.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, sz, vp]
+        L.caote_compact.restype = ctypes.c_int
+        L.caote_evict.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp]
+        L.caote_evict.restype = ctypes.c_int
+        L.caote_last_error.argtypes = []
+        L.caote_last_error.restype = ctypes.c_char_p
+        L.caote_version.argtypes = []
+        L.caote_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(st: int) -> None:
+    if st != OK:
+        raise CaoteError(st, lib().caote_last_error().decode())
+
+
+def _ptr(t) -> int | None:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> int | None:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def make_layout(q, K, V, *, base, softmax_scale, window_in_cache=1, pool_kernel=1,
+                n_protect_head=0, n_protect_tail=0, variant=EXACT, seq_lens=None) -> Layout:
+    """Layout of q [B,Hq,W,d], K/V [B,Hkv,cap,d] (innermost dimension contiguous)."""
+    B, Hq, W, d = q.shape
+    _, Hkv, cap, _ = K.shape
+    assert q.stride(3) == 1 and K.stride(3) == 1 and V.stride(3) == 1
+    assert q.dtype == K.dtype == V.dtype and q.dtype in (torch.bfloat16, torch.float32)
+    return Layout(
+        batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, window=W, capacity=cap,
+        seq_lens=_ptr(seq_lens),
+        k_stride_b=K.stride(0), k_stride_h=K.stride(1), k_stride_n=K.stride(2),
+        v_stride_b=V.stride(0), v_stride_h=V.stride(1), v_stride_n=V.stride(2),
+        q_stride_b=q.stride(0), q_stride_h=q.stride(1), q_stride_w=q.stride(2),
+        dtype=BF16 if q.dtype == torch.bfloat16 else F32, base=base,
+        softmax_scale=softmax_scale, pool_kernel=pool_kernel, window_in_cache=window_in_cache,
+        n_protect_head=n_protect_head, n_protect_tail=n_protect_tail, variant=variant)
+
+
+def caote_version() -> int:
+    return lib().caote_version()
+
+
+def caote_last_error() -> str:
+    return lib().caote_last_error().decode()
+
+
+def caote_workspace_bytes(layout: Layout, budget: int) -> int:
+    n = lib().caote_workspace_bytes(ctypes.byref(layout), budget)
+    if n == 0:
+        raise CaoteError(EINVAL, caote_last_error())
+    return n
+
+
+def caote_score(q_window, K, V, base_score, layout: Layout, scores, workspace, stream=None,
+                workspace_bytes=None) -> None:
+    wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().caote_score(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score), ctypes.byref(layout),
+                             _ptr(scores), _ptr(workspace), wb, _stream(stream)))
+
+
+def caote_select(scores, layout: Layout, budget: int, kept_idx, workspace, stream=None,
+                 workspace_bytes=None) -> None:
+    wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().caote_select(_ptr(scores), ctypes.byref(layout), budget, _ptr(kept_idx),
+                              _ptr(workspace), wb, _stream(stream)))
+
+
+def caote_compact(K, V, base_score, kept_idx, layout: Layout, budget: int, mode, workspace,
+                  stream=None, workspace_bytes=None) -> None:
+    wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().caote_compact(_ptr(K), _ptr(V), _ptr(base_score), _ptr(kept_idx),
+                               ctypes.byref(layout), budget, mode, _ptr(workspace), wb,
+                               _stream(stream)))
+
+
+def caote_evict(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores, kept_idx,
+                workspace, stream=None, workspace_bytes=None) -> None:
+    wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().caote_evict(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
+                             ctypes.byref(layout), budget, mode, _ptr(scores), _ptr(kept_idx),
+                             _ptr(workspace), wb, _stream(stream)))
+
+
+def layout_for(wl, cache_dev) -> Layout:
+    """Layout of a `synth.Cache` whose tensors live on the device, for workload `wl`."""
+    return make_layout(cache_dev.q, cache_dev.K, cache_dev.V, base=wl.base,
+                       softmax_scale=wl.softmax_scale, window_in_cache=wl.window_in_cache,
+                       pool_kernel=wl.pool_kernel, n_protect_head=wl.n_protect_head,
+                       n_protect_tail=wl.n_protect_tail, seq_lens=cache_dev.seq_lens)

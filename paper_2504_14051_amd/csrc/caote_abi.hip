@@ -1,0 +1,211 @@
+// C ABI of the CAOTE hot path: argument validation, workspace carving, launches.
+// No allocation, no synchronisation, no state between calls.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "common.hpp"
+
+using caote::Params;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+caote_status fail(caote_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+caote_status check_layout(const caote_layout* L, int32_t budget, bool need_budget) {
+  if (!L) return fail(CAOTE_EINVAL, "layout is NULL");
+  if (L->batch < 1 || L->n_q_heads < 1 || L->n_kv_heads < 1)
+    return fail(CAOTE_EINVAL, "batch, n_q_heads and n_kv_heads must be >= 1");
+  if (L->n_q_heads % L->n_kv_heads != 0)
+    return fail(CAOTE_EINVAL, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", L->n_q_heads,
+                L->n_kv_heads);
+  if (L->head_dim != 64 && L->head_dim != 128)
+    return fail(CAOTE_EUNSUPPORTED, "head_dim %d: only 64 and 128 are supported", L->head_dim);
+  if (L->window < 1) return fail(CAOTE_EINVAL, "window must be >= 1");
+  if (L->capacity < 1) return fail(CAOTE_EINVAL, "capacity must be >= 1");
+  if (L->dtype != CAOTE_BF16 && L->dtype != CAOTE_F32) return fail(CAOTE_EINVAL, "unknown dtype %d", L->dtype);
+  if (L->base < CAOTE_BASE_NONE || L->base > CAOTE_BASE_SNAPKV) return fail(CAOTE_EINVAL, "unknown base %d", L->base);
+  if (L->variant != CAOTE_EXACT && L->variant != CAOTE_FAST) return fail(CAOTE_EINVAL, "unknown variant %d", L->variant);
+  if (L->pool_kernel < 1 || L->pool_kernel % 2 == 0)
+    return fail(CAOTE_EINVAL, "pool_kernel must be odd and >= 1 (got %d)", L->pool_kernel);
+  if (L->n_protect_head < 0 || L->n_protect_tail < 0) return fail(CAOTE_EINVAL, "negative protected row count");
+  if (!(L->softmax_scale == L->softmax_scale) || isinf(L->softmax_scale))
+    return fail(CAOTE_EINVAL, "softmax_scale is not finite");
+  if (L->window_in_cache && !L->seq_lens && L->capacity < L->window)
+    return fail(CAOTE_EINVAL, "window (%d) exceeds the cache length (%d)", L->window, L->capacity);
+  const int esz = L->dtype == CAOTE_F32 ? 4 : 2;
+  const int64_t st[] = {L->k_stride_b, L->k_stride_h, L->k_stride_n, L->v_stride_b, L->v_stride_h,
+                        L->v_stride_n, L->q_stride_b, L->q_stride_h, L->q_stride_w};
+  for (int i = 0; i < 9; ++i) {
+    if (st[i] < 0) return fail(CAOTE_EINVAL, "negative stride");
+    if ((st[i] * esz) % 16 != 0) return fail(CAOTE_EINVAL, "strides must be multiples of 16 bytes");
+  }
+  if (L->k_stride_n < L->head_dim || L->v_stride_n < L->head_dim || L->q_stride_w < L->head_dim)
+    return fail(CAOTE_EINVAL, "row stride smaller than head_dim");
+  if ((int64_t)L->batch * L->n_kv_heads > 65535)
+    return fail(CAOTE_EUNSUPPORTED, "batch * n_kv_heads > 65535");
+  if (need_budget && budget < 1) return fail(CAOTE_EINVAL, "budget must be >= 1");
+  return CAOTE_OK;
+}
+
+// Fills the launch geometry and the workspace offsets of `p`; returns bytes needed.
+size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
+  memset(&p, 0, sizeof(p));
+  p.seq_lens = L->seq_lens;
+  p.B = L->batch; p.Hq = L->n_q_heads; p.Hkv = L->n_kv_heads; p.G = p.Hq / p.Hkv;
+  p.D = L->head_dim; p.W = L->window; p.R = p.G * p.W; p.cap = L->capacity;
+  p.ksb = L->k_stride_b; p.ksh = L->k_stride_h; p.ksn = L->k_stride_n;
+  p.vsb = L->v_stride_b; p.vsh = L->v_stride_h; p.vsn = L->v_stride_n;
+  p.qsb = L->q_stride_b; p.qsh = L->q_stride_h; p.qsw = L->q_stride_w;
+  p.base_mode = L->base; p.pool = L->pool_kernel; p.wic = L->window_in_cache ? 1 : 0;
+  p.ph = L->n_protect_head; p.pt = L->n_protect_tail; p.variant = L->variant; p.dtype = L->dtype;
+  p.budget = budget;
+  p.c2 = L->softmax_scale * 1.4426950408889634f;
+
+  const int BH = p.B * p.Hkv;
+  const int target = 1024;                       // workgroups wanted per launch
+  int n_split = ceil_div(target, BH);
+  n_split = n_split < 1 ? 1 : n_split;
+  int split_len = (int)align_up((size_t)ceil_div(p.cap, n_split), 64);
+  split_len = split_len < 256 ? 256 : (split_len > 8192 ? 8192 : split_len);
+  p.split_len = split_len;
+  p.n_split = ceil_div(p.cap, split_len);
+  p.vchunk_len = split_len;
+  p.n_vchunk = p.n_split;
+  p.Rp = (int)align_up((size_t)p.R, 32);
+
+  size_t off = 0;
+  auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return ws ? ws + o : nullptr; };
+  p.stats = (float*)carve((size_t)BH * p.n_split * p.Rp * 2 * sizeof(float));
+  p.lse2 = (float*)carve((size_t)BH * p.Rp * sizeof(float));
+  p.a = (float*)carve((size_t)BH * p.cap * sizeof(float));
+  p.h = (float*)carve((size_t)BH * p.cap * sizeof(float));
+  p.opart = (float*)carve((size_t)BH * p.n_vchunk * p.D * sizeof(float));
+  p.zpart = (float*)carve((size_t)BH * p.n_vchunk * sizeof(float));
+  p.sel = (uint32_t*)carve((size_t)BH * caote::kSelWords * sizeof(uint32_t));
+  const size_t row_bytes = (size_t)p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
+  const int bud = budget > 0 ? budget : 0;
+  p.stage = carve((size_t)BH * bud * (2 * row_bytes + sizeof(float)));
+  return off;
+}
+
+caote_status check_ws(const caote_layout* L, int32_t budget, void* ws, size_t ws_bytes, Params& p) {
+  if (!ws) return fail(CAOTE_EWORKSPACE, "workspace is NULL");
+  if (((uintptr_t)ws) % 256 != 0) return fail(CAOTE_EWORKSPACE, "workspace is not 256-byte aligned");
+  const size_t need = plan(L, budget, p, (char*)ws);
+  if (ws_bytes < need)
+    return fail(CAOTE_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+  return CAOTE_OK;
+}
+
+caote_status device_status(hipError_t e, const char* what) {
+  if (e == hipSuccess) return CAOTE_OK;
+  return fail(CAOTE_EDEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+caote_status do_score(Params& p, hipStream_t s) {
+  hipError_t e = caote::launch_score_generic(p, s);
+  if (e != hipSuccess) return device_status(e, "score (key sweeps)");
+  return device_status(caote::launch_value_passes(p, s), "score (value sweeps)");
+}
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+const char* caote_last_error(void) { return g_err; }
+
+int32_t caote_version(void) { return 100; }
+
+size_t caote_workspace_bytes(const caote_layout* layout, int32_t budget) {
+  if (check_layout(layout, budget, false) != CAOTE_OK) return 0;
+  Params p;
+  return plan(layout, budget, p, nullptr);
+}
+
+caote_status caote_score(const void* q_window, const void* K, const void* V, float* base_score,
+                         const caote_layout* layout, float* scores, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+  caote_status st = check_layout(layout, 0, false);
+  if (st != CAOTE_OK) return st;
+  if (!q_window || !K || !V || !scores) return fail(CAOTE_EINVAL, "q_window, K, V and scores must not be NULL");
+  if (layout->base == CAOTE_BASE_H2O && !base_score)
+    return fail(CAOTE_EINVAL, "CAOTE_BASE_H2O needs base_score (the accumulator)");
+  Params p;
+  st = check_ws(layout, 0, workspace, workspace_bytes, p);
+  if (st != CAOTE_OK) return st;
+  p.q = q_window; p.K = const_cast<void*>(K); p.V = const_cast<void*>(V);
+  p.base = base_score; p.scores = scores;
+  if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
+  return do_score(p, (hipStream_t)hip_stream);
+}
+
+caote_status caote_select(const float* scores, const caote_layout* layout, int32_t budget,
+                          int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                          void* hip_stream) {
+  caote_status st = check_layout(layout, budget, true);
+  if (st != CAOTE_OK) return st;
+  if (!scores || !kept_idx) return fail(CAOTE_EINVAL, "scores and kept_idx must not be NULL");
+  Params p;
+  st = check_ws(layout, budget, workspace, workspace_bytes, p);
+  if (st != CAOTE_OK) return st;
+  p.scores = const_cast<float*>(scores); p.kept = kept_idx;
+  return device_status(caote::launch_select(p, (hipStream_t)hip_stream), "select");
+}
+
+caote_status caote_compact(void* K, void* V, float* base_score, const int32_t* kept_idx,
+                           const caote_layout* layout, int32_t budget, int32_t mode,
+                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+  caote_status st = check_layout(layout, budget, true);
+  if (st != CAOTE_OK) return st;
+  if (!K || !V || !kept_idx) return fail(CAOTE_EINVAL, "K, V and kept_idx must not be NULL");
+  if (mode != CAOTE_COMPACT_STABLE && mode != CAOTE_COMPACT_SWAP_LAST)
+    return fail(CAOTE_EINVAL, "unknown compaction mode %d", mode);
+  Params p;
+  st = check_ws(layout, budget, workspace, workspace_bytes, p);
+  if (st != CAOTE_OK) return st;
+  p.K = K; p.V = V; p.base = base_score; p.kept = const_cast<int32_t*>(kept_idx); p.mode = mode;
+  return device_status(caote::launch_compact(p, (hipStream_t)hip_stream), "compact");
+}
+
+caote_status caote_evict(const void* q_window, void* K, void* V, float* base_score,
+                         const caote_layout* layout, int32_t budget, int32_t mode, float* scores,
+                         int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  caote_status st = check_layout(layout, budget, true);
+  if (st != CAOTE_OK) return st;
+  if (!q_window || !K || !V || !scores || !kept_idx)
+    return fail(CAOTE_EINVAL, "q_window, K, V, scores and kept_idx must not be NULL");
+  if (layout->base == CAOTE_BASE_H2O && !base_score)
+    return fail(CAOTE_EINVAL, "CAOTE_BASE_H2O needs base_score (the accumulator)");
+  if (mode != CAOTE_COMPACT_STABLE && mode != CAOTE_COMPACT_SWAP_LAST)
+    return fail(CAOTE_EINVAL, "unknown compaction mode %d", mode);
+  Params p;
+  st = check_ws(layout, budget, workspace, workspace_bytes, p);
+  if (st != CAOTE_OK) return st;
+  p.q = q_window; p.K = K; p.V = V; p.base = base_score; p.scores = scores; p.kept = kept_idx;
+  p.mode = mode;
+  if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
+  hipStream_t s = (hipStream_t)hip_stream;
+  st = do_score(p, s);
+  if (st != CAOTE_OK) return st;
+  st = device_status(caote::launch_select(p, s), "select");
+  if (st != CAOTE_OK) return st;
+  return device_status(caote::launch_compact(p, s), "compact");
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

@@ -1,0 +1,87 @@
+// Shared declarations of the CAOTE HIP kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "caote.h"
+
+namespace caote {
+
+constexpr int kWave = 64;
+
+// Everything a kernel needs to know about one call.  Passed by value.
+struct Params {
+  const void* q;
+  void* K;
+  void* V;
+  float* base;        // H2O accumulator (in/out) or nullptr
+  float* scores;      // out
+  const int32_t* seq_lens;
+  int32_t* kept;      // [BH][budget]
+  int B, Hq, Hkv, G, D, W, R, cap;
+  int64_t ksb, ksh, ksn, vsb, vsh, vsn, qsb, qsh, qsw;
+  int base_mode, pool, wic, ph, pt, variant, dtype;
+  int budget, mode;
+  float c2;           // softmax_scale * log2(e): logits are handled in the log2 domain
+  // ---- workspace ----
+  float* stats;       // [BH][n_split][Rp][2]  partial (max, sum) per query row
+  float* lse2;        // [BH][Rp]              log2-sum-exp2 per query row
+  float* a;           // [BH][cap]             column sums of attention
+  float* h;           // [BH][cap]             base score (aliases `base` for H2O)
+  float* opart;       // [BH][n_vchunk][D]     partial sum of h_j v_j
+  float* zpart;       // [BH][n_vchunk]        partial sum of h_j
+  uint32_t* sel;      // [BH][kSelWords]       selection scratch (threshold etc.)
+  void* stage;        // compaction staging
+  int n_split, split_len, Rp, n_vchunk, vchunk_len;
+};
+
+// Per-(sequence, head) selection record written by the threshold search.
+constexpr int kSelWords = 8;   // [0] threshold key, [1] #ties to keep, [2] n_keep
+
+__device__ __forceinline__ int seq_len(const Params& p, int b) {
+  if (p.seq_lens == nullptr) return p.cap;
+  int n = p.seq_lens[b];
+  return n < 0 ? 0 : (n > p.cap ? p.cap : n);
+}
+
+// ---- 8-element row fragments ---------------------------------------------------
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ void load8(const float* ptr, float (&x)[8]) {
+  const float4 lo = *reinterpret_cast<const float4*>(ptr);
+  const float4 hi = *reinterpret_cast<const float4*>(ptr + 4);
+  x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
+  x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+}
+
+__device__ __forceinline__ void load8(const bf16_t* ptr, float (&x)[8]) {
+  const uint4 u = *reinterpret_cast<const uint4*>(ptr);
+  x[0] = __uint_as_float(u.x << 16); x[1] = __uint_as_float(u.x & 0xffff0000u);
+  x[2] = __uint_as_float(u.y << 16); x[3] = __uint_as_float(u.y & 0xffff0000u);
+  x[4] = __uint_as_float(u.z << 16); x[5] = __uint_as_float(u.z & 0xffff0000u);
+  x[6] = __uint_as_float(u.w << 16); x[7] = __uint_as_float(u.w & 0xffff0000u);
+}
+
+// Sum over a team of TL consecutive lanes (TL a power of two <= 64); every lane
+// of the team receives the total.
+template <int TL>
+__device__ __forceinline__ float team_sum(float v) {
+#pragma unroll
+  for (int m = TL / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+
+// Order-preserving map float -> uint32 (larger float <=> larger key).
+__device__ __forceinline__ uint32_t float_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// ---- launchers (one per source file) --------------------------------------------
+hipError_t launch_score_generic(const Params& p, hipStream_t s);
+hipError_t launch_value_passes(const Params& p, hipStream_t s);
+hipError_t launch_select(const Params& p, hipStream_t s);
+hipError_t launch_compact(const Params& p, hipStream_t s);
+
+}  // namespace caote

@@ -1,0 +1,80 @@
+// In-place cache update after selection (Sec. 2: attention afterwards uses only the
+// kept rows i_1..i_b): rows of K, V and the H2O accumulator move to the front of
+// their slab.
+//
+// kept_idx is ascending, so rank i reads row kept_idx[i] >= i and writes row i; a
+// row may be overwritten by one rank while another rank still has to read it.  The
+// rows that move are therefore first gathered into staging memory and written back
+// by a second kernel (stream order is the barrier).  Rows that already sit at their
+// rank are not touched.
+//
+// Evict-one sequences in SWAP_LAST mode move a single row: the last row drops into
+// the hole.  A sequence that evicts any other number of tokens is compacted stably.
+#include "common.hpp"
+
+namespace caote {
+namespace {
+
+constexpr int kThreads = 256;
+
+// Source row of rank i, or -1 if rank i does not move.
+__device__ __forceinline__ int source_row(const Params& p, const int32_t* idx, int i, int N) {
+  const int n_keep = min(N, p.budget);
+  if (i >= n_keep) return -1;
+  const int src = idx[i];
+  if (p.mode == CAOTE_COMPACT_SWAP_LAST && N - n_keep == 1) {
+    const bool first_hole = src != i && (i == 0 || idx[i - 1] == i - 1);
+    return first_hole ? N - 1 : -1;
+  }
+  return src == i ? -1 : src;
+}
+
+// dir 0: cache -> staging, dir 1: staging -> cache.
+template <int DIR>
+__global__ __launch_bounds__(kThreads) void k_move_rows(const Params p, int row_bytes) {
+  const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
+  const int N = seq_len(p, b);
+  const int cpr = row_bytes / 16;                     // 16-byte chunks per row
+  const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int i = (int)(id / cpr), ch = (int)(id % cpr);
+  if (i >= p.budget) return;
+  const int32_t* idx = p.kept + (int64_t)bh * p.budget;
+  const int src = source_row(p, idx, i, N);
+  if (src < 0) return;
+
+  const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
+  char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
+  char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
+  char* stK = reinterpret_cast<char*>(p.stage) + (int64_t)bh * p.budget * row_bytes;
+  char* stV = stK + (int64_t)p.B * p.Hkv * p.budget * row_bytes;
+  float* stB = reinterpret_cast<float*>(reinterpret_cast<char*>(p.stage) +
+                                        2 * (int64_t)p.B * p.Hkv * p.budget * row_bytes) +
+               (int64_t)bh * p.budget;
+  const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
+  if (DIR == 0) {
+    *reinterpret_cast<uint4*>(stK + (int64_t)i * row_bytes + ch * 16) =
+        *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
+    *reinterpret_cast<uint4*>(stV + (int64_t)i * row_bytes + ch * 16) =
+        *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
+    if (ch == 0 && p.base) stB[i] = p.base[(int64_t)bh * p.cap + src];
+  } else {
+    *reinterpret_cast<uint4*>(Kb + i * krow + ch * 16) =
+        *reinterpret_cast<const uint4*>(stK + (int64_t)i * row_bytes + ch * 16);
+    *reinterpret_cast<uint4*>(Vb + i * vrow + ch * 16) =
+        *reinterpret_cast<const uint4*>(stV + (int64_t)i * row_bytes + ch * 16);
+    if (ch == 0 && p.base) p.base[(int64_t)bh * p.cap + i] = stB[i];
+  }
+}
+
+}  // namespace
+
+hipError_t launch_compact(const Params& p, hipStream_t s) {
+  const int row_bytes = p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
+  const int64_t chunks = (int64_t)p.budget * (row_bytes / 16);
+  const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads), p.B * p.Hkv);
+  hipLaunchKernelGGL(k_move_rows<0>, grid, dim3(kThreads), 0, s, p, row_bytes);
+  hipLaunchKernelGGL(k_move_rows<1>, grid, dim3(kThreads), 0, s, p, row_bytes);
+  return hipGetLastError();
+}
+
+}  // namespace caote

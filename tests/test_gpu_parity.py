@@ -1,0 +1,267 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle on
+the same seeded inputs.  Comparison rules are in tests/helpers.py."""
+import numpy as np
+import pytest
+import torch
+
+import helpers as H
+from paper_2504_14051_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2504_14051_amd import binding
+    binding.lib()
+    assert torch.cuda.is_available()
+    return binding
+
+
+def run_path(B, cache, budget, mode=0, variant=0, fused=False):
+    """Runs score -> select -> compact on the device.  Returns host copies of every stage."""
+    wl = cache.wl
+    dev = H.to_device(cache)
+    L = B.layout_for(wl, dev)
+    L.variant = variant
+    nb = B.caote_workspace_bytes(L, budget)
+    ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    Bn, Hkv, cap = dev.K.shape[:3]
+    scores = torch.full((Bn, Hkv, cap), float("nan"), device="cuda")
+    kept = torch.full((Bn, Hkv, budget), -7, dtype=torch.int32, device="cuda")
+    base = dev.base if wl.base == synth.BASE_H2O else None
+    out = {}
+    if fused:
+        B.caote_evict(dev.q, dev.K, dev.V, base, L, budget, mode, scores, kept, ws)
+    else:
+        B.caote_score(dev.q, dev.K, dev.V, base, L, scores, ws)
+        B.caote_select(scores, L, budget, kept, ws)
+        torch.cuda.synchronize()
+        out["K_before"], out["V_before"] = dev.K.cpu(), dev.V.cpu()
+        out["base_before"] = None if base is None else base.cpu()
+        B.caote_compact(dev.K, dev.V, base, kept, L, budget, mode, ws)
+    torch.cuda.synchronize()
+    out.update(scores=scores.cpu().numpy(), kept=kept.cpu().numpy(), K_after=dev.K.cpu(),
+               V_after=dev.V.cpu(), base_after=None if base is None else base.cpu())
+    return out
+
+
+def full_check(B, oracle, cache, budget, mode=0, variant=0):
+    wl = cache.wl
+    rtol = H.RTOL[wl.dtype]
+    res = run_path(B, cache, budget, mode, variant)
+    oc, oh, oa = H.oracle_scores(oracle, cache, variant)
+    worst = H.check_scores(res["scores"], oc, oh, cache, rtol)
+    H.check_kept(res["kept"], oc, cache, budget, rtol, gpu_scores=res["scores"])
+    if wl.base == synth.BASE_H2O:        # the accumulator now holds h for every row
+        for b, N in enumerate(H.lengths(cache)):
+            np.testing.assert_allclose(res["base_before"][b, :, :N].numpy(), oh[b, :, :N],
+                                       rtol=rtol, atol=1e-7)
+    H.check_compaction(oracle, res["K_before"], res["V_before"], res["base_before"],
+                       res["K_after"], res["V_after"], res["base_after"], res["kept"], cache,
+                       budget, "swap_last" if mode == 1 else "stable")
+    # rows past each sequence's length are never written
+    for b, N in enumerate(H.lengths(cache)):
+        assert np.isnan(res["scores"][b, :, N:]).all()
+    # the fused entry point gives the same bits
+    fz = run_path(B, cache, budget, mode, variant, fused=True)
+    for key in ("scores", "kept"):
+        assert np.array_equal(res[key], fz[key], equal_nan=True), f"caote_evict differs in {key}"
+    for b, N in enumerate(H.lengths(cache)):
+        n_keep = min(N, budget)
+        for key in ("K_after", "V_after"):
+            assert torch.equal(res[key][b, :, :n_keep].view(torch.int16 if wl.dtype == "bf16" else torch.int32),
+                               fz[key][b, :, :n_keep].view(torch.int16 if wl.dtype == "bf16" else torch.int32))
+    return worst
+
+
+def small(**kw):
+    base = dict(name="small", batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, dtype="bf16",
+                context=700, window=8, budget=200, base=synth.BASE_H2O, seed=77)
+    base.update(kw)
+    return synth.Workload(**base)
+
+
+# ---- the named configurations ------------------------------------------------------
+
+def test_tiny_fp32_h2o(B, oracle):
+    wl = synth.tiny()
+    worst = full_check(B, oracle, synth.make_cache(wl), wl.budget)
+    assert worst < 2e-4
+
+
+def test_llama3_8b_4k_h2o(B, oracle):
+    wl = synth.llama3_8b_4k()
+    full_check(B, oracle, synth.make_cache(wl), wl.budget)
+
+
+def test_llama3_8b_32k_snapkv(B, oracle):
+    wl = synth.llama3_8b_32k()
+    full_check(B, oracle, synth.make_cache(wl), wl.budget)
+
+
+def test_qwen25_7b_128k_snapkv(B, oracle):
+    wl = synth.qwen25_7b_128k()
+    full_check(B, oracle, synth.make_cache(wl), wl.budget)
+
+
+def test_decode_stream_steps(B, oracle):
+    """Decode-time eviction: caches at budget+1, one query, evict one token per head with the
+    last row dropping into the hole; several steps, the oracle restarted from the GPU's
+    state at every step so that rounding does not pile up."""
+    wl = synth.decode_step(batch=3)
+    cache = synth.make_cache(wl, base_init="random")
+    for step in range(4):
+        full_check(B, oracle, cache, wl.budget, mode=1)
+        res = run_path(B, cache, wl.budget, mode=1)
+        fresh = synth.make_cache(wl, layer=step + 1, base_init="random")
+        K, V, base = res["K_after"].clone(), res["V_after"].clone(), res["base_after"].clone()
+        K[:, :, -1], V[:, :, -1] = fresh.K[:, :, -1], fresh.V[:, :, -1]     # appended token
+        base[:, :, -1] = 0.0
+        cache = synth.Cache(wl, fresh.q, K, V, base, None)
+
+
+# ---- shapes, modes, edges -------------------------------------------------------------
+
+@pytest.mark.parametrize("kw", [
+    dict(),                                                       # H2O, ragged below
+    dict(base=synth.BASE_NONE),
+    dict(base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=8),
+    dict(base=synth.BASE_SNAPKV, pool_kernel=5, n_protect_tail=8, n_protect_head=4),
+    dict(base=synth.BASE_H2O, n_protect_head=3, n_protect_tail=2),
+    dict(head_dim=64),
+    dict(head_dim=64, dtype="f32", base=synth.BASE_SNAPKV, pool_kernel=3, n_protect_tail=8),
+    dict(dtype="f32"),
+    dict(n_q_heads=14, n_kv_heads=2, window=5),                   # G = 7, R = 35
+    dict(window=1, n_q_heads=2, n_kv_heads=2, base=synth.BASE_NONE),   # TOVA
+    dict(window_in_cache=0),
+], ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()) or "h2o")
+def test_small_shapes_ragged(B, oracle, kw):
+    wl = small(**kw)
+    lens = np.array([wl.context, 333], dtype=np.int32)
+    cache = synth.make_cache(wl, seq_lens=lens, base_init="random")
+    full_check(B, oracle, cache, wl.budget)
+
+
+def test_fastcaote_variant(B, oracle):
+    wl = small(base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=8)
+    full_check(B, oracle, synth.make_cache(wl), wl.budget, variant=1)
+    wl = small()
+    full_check(B, oracle, synth.make_cache(wl, base_init="random"), wl.budget, variant=1)
+
+
+@pytest.mark.parametrize("lens,budget", [
+    ([700, 8], 200),        # second sequence: only the window, shorter than the budget
+    ([300, 0], 200),        # an empty sequence is skipped
+    ([201, 200], 200),      # evict exactly one / evict none
+    ([700, 699], 1),        # budget of one
+    ([700, 700], 699),      # budget N-1
+    ([512, 256], 256),      # tile-aligned lengths
+    ([513, 257], 250),
+])
+def test_length_and_budget_edges(B, oracle, lens, budget):
+    wl = small(budget=budget)
+    lens = np.array(lens, dtype=np.int32)
+    host_lens = np.maximum(lens, wl.window)       # the generator needs N >= W
+    cache = synth.make_cache(wl, seq_lens=host_lens, base_init="random")
+    cache.seq_lens = torch.as_tensor(lens)
+    if (lens < wl.window).any():
+        # a sequence shorter than the window breaks the caller's contract for
+        # window_in_cache; run it with every key visible instead
+        cache = synth.Cache(wl.with_(window_in_cache=0), cache.q, cache.K, cache.V, cache.base,
+                            cache.seq_lens)
+    full_check(B, oracle, cache, budget)
+
+
+def test_all_rows_protected_and_single_scored_token(B, oracle):
+    wl = small(context=64, budget=40, n_protect_head=30, n_protect_tail=34, batch=1)
+    full_check(B, oracle, synth.make_cache(wl), wl.budget)
+    wl = small(context=64, budget=40, n_protect_head=30, n_protect_tail=33, batch=1)
+    full_check(B, oracle, synth.make_cache(wl), wl.budget)
+
+
+def test_strided_views(B, oracle):
+    """K and V as slices of a larger allocation (row stride > head_dim)."""
+    wl = small(batch=1)
+    cache = synth.make_cache(wl)
+    padK = torch.zeros(1, 2, wl.context, 256, dtype=cache.K.dtype)
+    padV = torch.zeros(1, 2, wl.context, 256, dtype=cache.K.dtype)
+    padK[..., :128], padV[..., 128:] = cache.K, cache.V
+    dev = H.to_device(cache)
+    dK, dV = padK.cuda()[..., :128], padV.cuda()[..., 128:]
+    assert dK.stride(2) == 256
+    L = B.make_layout(dev.q, dK, dV, base=wl.base, softmax_scale=wl.softmax_scale)
+    ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
+    s1 = torch.empty(1, 2, wl.context, device="cuda")
+    s2 = torch.empty_like(s1)
+    b1, b2 = dev.base.clone(), dev.base.clone()
+    B.caote_score(dev.q, dK, dV, b1, L, s1, ws)
+    L2 = B.layout_for(wl, dev)
+    B.caote_score(dev.q, dev.K, dev.V, b2, L2, s2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(s1, s2) and torch.equal(b1, b2)
+
+
+def test_deterministic_bits(B):
+    wl = synth.llama3_8b_4k()
+    cache = synth.make_cache(wl)
+    r1 = run_path(B, cache, wl.budget, fused=True)
+    r2 = run_path(B, cache, wl.budget, fused=True)
+    assert np.array_equal(r1["scores"], r2["scores"]) and np.array_equal(r1["kept"], r2["kept"])
+    assert torch.equal(r1["K_after"].view(torch.int16), r2["K_after"].view(torch.int16))
+
+
+# ---- select and compact on their own ------------------------------------------------------
+
+def _layout_only(B, batch, hkv, cap, d=128, dtype=torch.bfloat16):
+    q = torch.empty(batch, hkv, 1, d, dtype=dtype, device="cuda")
+    K = torch.empty(batch, hkv, cap, d, dtype=dtype, device="cuda")
+    return B.make_layout(q, K, K, base=B.BASE_NONE, softmax_scale=1.0), K
+
+
+@pytest.mark.parametrize("cap,budget", [(1, 1), (63, 10), (1000, 999), (5000, 1234), (40000, 2048),
+                                        (131072, 4096), (300000, 100000)])
+def test_select_exact_with_ties_and_infinities(B, oracle, cap, budget):
+    rng = np.random.default_rng(cap)
+    sc = rng.standard_normal((2, 3, cap)).astype(np.float32)
+    sc[0, 0] = np.round(sc[0, 0], 1)                   # many ties (incl. +-0)
+    sc[0, 1] = np.abs(sc[0, 1]) * 1e-30                # tiny positives, same exponent range
+    sc[0, 2, :] = 1.5                                  # all equal
+    sc[1, 0, rng.integers(0, cap, size=max(1, cap // 50))] = np.inf
+    sc[1, 1, rng.integers(0, cap, size=max(1, cap // 3))] = 0.0
+    sc[1, 2] = -np.abs(sc[1, 2])                       # negatives sort correctly too
+    L, _ = _layout_only(B, 2, 3, cap)
+    ws = torch.empty(B.caote_workspace_bytes(L, budget), dtype=torch.uint8, device="cuda")
+    kept = torch.full((2, 3, budget), -7, dtype=torch.int32, device="cuda")
+    B.caote_select(torch.from_numpy(sc).cuda(), L, budget, kept, ws)
+    torch.cuda.synchronize()
+    kept = kept.cpu().numpy()
+    ref = oracle.select_batched(sc.astype(np.float64), None, budget)
+    assert np.array_equal(kept, ref)
+
+
+@pytest.mark.parametrize("pattern", ["identity", "tail", "every_other", "head_then_tail", "shift_one"])
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64), (torch.bfloat16, 64)])
+def test_compact_hazard_patterns(B, oracle, pattern, dtype, d):
+    cap, budget = 3000, 1400
+    idx = {
+        "identity": np.arange(budget),
+        "tail": np.arange(cap - budget, cap),
+        "every_other": np.arange(0, 2 * budget, 2),
+        "head_then_tail": np.concatenate([np.arange(700), np.arange(cap - 700, cap)]),
+        "shift_one": np.arange(1, budget + 1),
+    }[pattern].astype(np.int32)
+    L, _ = _layout_only(B, 1, 2, cap, d, dtype)
+    g = torch.Generator().manual_seed(5)
+    K = torch.randn(1, 2, cap, d, generator=g).to(dtype)
+    V = torch.randn(1, 2, cap, d, generator=g).to(dtype)
+    base = torch.rand(1, 2, cap, generator=g)
+    kept = torch.from_numpy(np.tile(idx, (1, 2, 1)))
+    dK, dV, db = K.cuda(), V.cuda(), base.cuda()
+    L = B.make_layout(torch.empty(1, 2, 1, d, dtype=dtype, device="cuda"), dK, dV, base=B.BASE_NONE,
+                      softmax_scale=1.0)
+    ws = torch.empty(B.caote_workspace_bytes(L, budget), dtype=torch.uint8, device="cuda")
+    B.caote_compact(dK, dV, db, kept.cuda(), L, budget, B.COMPACT_STABLE, ws)
+    torch.cuda.synchronize()
+    cache = synth.Cache(None, None, K, V, base, None)
+    H.check_compaction(oracle, K, V, base, dK.cpu(), dV.cpu(), db.cpu(), kept.numpy(), cache, budget)
