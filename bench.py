@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the CAOTE hot path on one MI355X.
+
+A step = one fused score + select + compact call (caote_evict) over one layer's KV
+cache (all KV heads) of synthetic data already resident in HBM.  Steps rotate over
+several independent layer buffers so that K and V come from HBM, not from the 256 MB
+Infinity Cache.  Prints ONE JSON line:
+
+  metric/value  cached tokens scored+evicted per second per layer (all heads)
+  roofline      the slowest kernel of the path: its own compulsory HBM bytes / its mean
+                duration (HIP events on the launch stream) against the 8 TB/s peak
+  path          the whole path's algorithmic bytes / step time against the same peak
+  cpu_baseline  the fp64 oracle on the host cores, same workload (a reported baseline,
+                not a target)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(wl, n_tokens=None):
+    """HBM bytes the method must move for one layer (K and V once, window queries, three
+    fp32 per-token vectors, gather read + write of the kept rows)."""
+    N = wl.context if n_tokens is None else n_tokens
+    esz = 2 if wl.dtype == "bf16" else 4
+    bh = wl.batch * wl.n_kv_heads
+    kv = 2 * bh * N * wl.head_dim * esz
+    q = wl.batch * wl.n_q_heads * wl.window * wl.head_dim * esz
+    vec = 3 * bh * N * 4
+    comp = 2 * 2 * bh * min(wl.budget, N) * wl.head_dim * esz
+    return {"kv": kv, "q": q, "vectors": vec, "compact": comp, "total": kv + q + vec + comp}
+
+
+def phase_bytes(wl, name):
+    """Compulsory HBM bytes of one kernel of the path, given that its inputs live in HBM."""
+    N, d, esz = wl.context, wl.head_dim, (2 if wl.dtype == "bf16" else 4)
+    bh = wl.batch * wl.n_kv_heads
+    R = wl.group * wl.window
+    k_bytes = bh * N * d * esz
+    q_bytes = wl.batch * wl.n_q_heads * wl.window * d * esz
+    vec = bh * N * 4
+    rows = bh * min(wl.budget, N) * d * esz
+    table = {
+        "key_rowstats": k_bytes + q_bytes,
+        "merge_stats": bh * R * 8,
+        "key_colsum": k_bytes + q_bytes + vec,
+        "key_sweeps": k_bytes + q_bytes + vec,          # fused: K from HBM once
+        "value_sum": k_bytes + 2 * vec,
+        "value_score": k_bytes + 2 * vec,
+        "value_sweeps": k_bytes + 3 * vec,
+        "select": vec + bh * wl.budget * 4,
+        "compact_gather": 2 * 2 * rows,
+        "compact_scatter": 2 * 2 * rows,
+        "compact": 2 * 2 * rows,
+        "evict_fused": algorithmic_bytes(wl)["total"],
+    }
+    return table.get(name)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama3-8b-32k")
+    ap.add_argument("--layers", type=int, default=16, help="independent layer buffers to rotate over")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU by design (each (sequence, layer, KV head) is "
+              "independent; see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2504_14051_amd import binding as B
+    from paper_2504_14051_amd import synth
+
+    B.lib()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]()
+    host = synth.make_cache(wl)
+    n_layers = max(1, args.layers)
+    mode = B.COMPACT_SWAP_LAST if wl.window == 1 and wl.budget == wl.context - 1 else B.COMPACT_STABLE
+
+    # Layer 0 is the generator's output; the others are the same tensors with the KV heads
+    # rotated (same statistics, different addresses), so each step streams fresh HBM lines.
+    G = wl.group
+    layers = []
+    for l in range(n_layers):
+        sh = l % wl.n_kv_heads
+        K = torch.roll(host.K, sh, dims=1).cuda()
+        V = torch.roll(host.V, sh, dims=1).cuda()
+        q = torch.roll(host.q, sh * G, dims=1).cuda()
+        base = torch.roll(host.base, sh, dims=1).cuda() if wl.base == synth.BASE_H2O else None
+        layers.append((q, K, V, base))
+    q0, K0, V0, _ = layers[0]
+    L = B.make_layout(q0, K0, V0, base=wl.base, softmax_scale=wl.softmax_scale,
+                      window_in_cache=wl.window_in_cache, pool_kernel=wl.pool_kernel,
+                      n_protect_head=wl.n_protect_head, n_protect_tail=wl.n_protect_tail)
+    ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
+    scores = torch.empty(wl.batch, wl.n_kv_heads, wl.context, device="cuda")
+    kept = torch.empty(wl.batch, wl.n_kv_heads, wl.budget, dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        q, K, V, base = layers[i % n_layers]
+        B.caote_evict(q, K, V, base, L, wl.budget, mode, scores, kept, ws, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    tokens_per_s = wl.batch * wl.context / (dt / args.steps)
+
+    # Per-kernel durations: the same call with a HIP event between its kernels, on the
+    # stream the kernels run on, over the same rotation of buffers.
+    n_timed = max(10, min(args.steps, 100))
+    acc = {}
+    for i in range(n_timed):
+        q, K, V, base = layers[i % n_layers]
+        for name, ms in B.caote_evict_timed(q, K, V, base, L, wl.budget, mode, scores, kept, ws, stream):
+            acc.setdefault(name, []).append(ms)
+    phases = {k: sum(v) / len(v) for k, v in acc.items()}
+    dom = max(phases, key=phases.get)
+    dom_bytes = phase_bytes(wl, dom)
+    dom_gbs = dom_bytes / (phases[dom] * 1e-3) / 1e9
+    alg = algorithmic_bytes(wl)
+    path_gbs = alg["total"] / (ms_per_step * 1e-3) / 1e9
+
+    out = {
+        "metric": "cached tokens scored+evicted/sec per layer (all heads); % of HBM peak",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "n_q_heads": wl.n_q_heads, "n_kv_heads": wl.n_kv_heads,
+                   "head_dim": wl.head_dim, "context": wl.context, "window": wl.window,
+                   "budget": wl.budget, "base": {0: "none", 1: "h2o", 2: "snapkv"}[wl.base],
+                   "pool_kernel": wl.pool_kernel, "batch": wl.batch, "layer_buffers": n_layers,
+                   "entry_point": "caote_evict"},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": dom_bytes, "ms_per_launch": phases[dom]},
+        "path": {"algorithmic_bytes": alg["total"], "achieved": path_gbs, "peak": HBM_PEAK_GBS,
+                 "unit": "GB/s", "frac": path_gbs / HBM_PEAK_GBS},
+        "phases_ms": phases,
+    }
+
+    if not args.skip_cpu_baseline:
+        import oracle
+        sys.path.insert(0, os.path.join(ROOT, "tests"))
+        import helpers as H
+        oracle.build()
+        threads = H.host_threads()
+        t0 = time.perf_counter()
+        oc, oh, _ = H.oracle_scores(oracle, host, threads=threads)
+        kept_o = oracle.select_batched(oc, None, wl.budget)
+        for hk in range(wl.n_kv_heads):
+            oracle.compact_one(host.K[0, hk].view(torch.uint8).numpy(), kept_o[0, hk])
+            oracle.compact_one(host.V[0, hk].view(torch.uint8).numpy(), kept_o[0, hk])
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": wl.batch * wl.context / t_cpu, "unit": "tokens/s", "cores": threads,
+            "kind": "oracle", "seconds": t_cpu,
+            "sample": f"one whole layer of the same workload (sequence 0, all {wl.n_kv_heads} KV heads): "
+                      "score + select + compact"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -145,6 +145,20 @@ caote_status caote_evict(const void* q_window, void* K, void* V, float* base_sco
                          float* scores, int32_t* kept_idx, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
 
+/* Measurement aid (benchmarks, profiling): caote_evict with a HIP event recorded
+ * on `hip_stream` between its kernels.  Unlike every other entry point it creates
+ * and destroys HIP events and WAITS for the stream before returning.
+ *   phase_ms  HOST out [CAOTE_MAX_PHASES]: milliseconds between consecutive events
+ *   n_phases  HOST out: number of phases filled in
+ * caote_phase_name(i) names phase i of the calling thread's last timed call.      */
+#define CAOTE_MAX_PHASES 16
+caote_status caote_evict_timed(const void* q_window, void* K, void* V, float* base_score,
+                               const caote_layout* layout, int32_t budget, int32_t mode,
+                               float* scores, int32_t* kept_idx, void* workspace,
+                               size_t workspace_bytes, void* hip_stream, float* phase_ms,
+                               int32_t* n_phases);
+const char* caote_phase_name(int32_t i);
+
 /* Text of the calling thread's most recent failure ("" if none).  The pointer
  * stays valid until that thread's next failing call.                               */
 const char* caote_last_error(void);

@@ -22,7 +22,9 @@ EXACT, FAST = 0, 1
 COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
 
 EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
-           "caote_evict", "caote_last_error", "caote_version")
+           "caote_evict", "caote_evict_timed", "caote_phase_name", "caote_last_error",
+           "caote_version")
+MAX_PHASES = 16
 
 
 class CaoteError(RuntimeError):
@@ -70,6 +72,11 @@ def lib() -> ctypes.CDLL:
         L.caote_compact.restype = ctypes.c_int
         L.caote_evict.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp]
         L.caote_evict.restype = ctypes.c_int
+        L.caote_evict_timed.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp,
+                                        ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        L.caote_evict_timed.restype = ctypes.c_int
+        L.caote_phase_name.argtypes = [i32]
+        L.caote_phase_name.restype = ctypes.c_char_p
         L.caote_last_error.argtypes = []
         L.caote_last_error.restype = ctypes.c_char_p
         L.caote_version.argtypes = []
@@ -160,6 +167,20 @@ def caote_evict(q_window, K, V, base_score, layout: Layout, budget: int, mode, s
     _check(lib().caote_evict(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
                              ctypes.byref(layout), budget, mode, _ptr(scores), _ptr(kept_idx),
                              _ptr(workspace), wb, _stream(stream)))
+
+
+def caote_evict_timed(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores,
+                      kept_idx, workspace, stream=None, workspace_bytes=None):
+    """caote_evict with HIP events between its kernels; waits for the stream.
+    Returns [(phase name, milliseconds), ...]."""
+    wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    ms = (ctypes.c_float * MAX_PHASES)()
+    n = ctypes.c_int32(0)
+    _check(lib().caote_evict_timed(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
+                                   ctypes.byref(layout), budget, mode, _ptr(scores),
+                                   _ptr(kept_idx), _ptr(workspace), wb, _stream(stream), ms,
+                                   ctypes.byref(n)))
+    return [(lib().caote_phase_name(i).decode(), float(ms[i])) for i in range(n.value)]
 
 
 def layout_for(wl, cache_dev) -> Layout:

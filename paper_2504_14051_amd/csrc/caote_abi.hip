@@ -115,11 +115,36 @@ caote_status device_status(hipError_t e, const char* what) {
   return fail(CAOTE_EDEVICE, "%s: %s", what, hipGetErrorString(e));
 }
 
-caote_status do_score(Params& p, hipStream_t s) {
-  hipError_t e = caote::launch_score_generic(p, s);
+caote_status do_score(Params& p, hipStream_t s, caote::PhaseHook* hook = nullptr) {
+  hipError_t e = caote::launch_score_generic(p, s, hook);
   if (e != hipSuccess) return device_status(e, "score (key sweeps)");
-  return device_status(caote::launch_value_passes(p, s), "score (value sweeps)");
+  return device_status(caote::launch_value_passes(p, s, hook), "score (value sweeps)");
 }
+
+// Measurement aid: events recorded between the kernels of one call.
+struct PhaseClock final : caote::PhaseHook {
+  hipStream_t stream;
+  hipEvent_t ev[CAOTE_MAX_PHASES + 1];
+  const char* names[CAOTE_MAX_PHASES];
+  int n = 0, n_ev = 0;
+  bool ok = true;
+  explicit PhaseClock(hipStream_t s) : stream(s) {
+    for (auto& e : ev) {
+      if (hipEventCreate(&e) != hipSuccess) { ok = false; break; }
+      ++n_ev;
+    }
+    if (ok) ok = hipEventRecord(ev[0], stream) == hipSuccess;
+  }
+  ~PhaseClock() { for (int i = 0; i < n_ev; ++i) (void)hipEventDestroy(ev[i]); }
+  void mark(const char* name) override {
+    if (!ok || n >= CAOTE_MAX_PHASES) return;
+    names[n] = name;
+    ok = hipEventRecord(ev[n + 1], stream) == hipSuccess;
+    ++n;
+  }
+};
+
+thread_local const char* g_phase_names[CAOTE_MAX_PHASES] = {};
 
 }  // namespace
 
@@ -163,7 +188,7 @@ caote_status caote_select(const float* scores, const caote_layout* layout, int32
   st = check_ws(layout, budget, workspace, workspace_bytes, p);
   if (st != CAOTE_OK) return st;
   p.scores = const_cast<float*>(scores); p.kept = kept_idx;
-  return device_status(caote::launch_select(p, (hipStream_t)hip_stream), "select");
+  return device_status(caote::launch_select(p, (hipStream_t)hip_stream, nullptr), "select");
 }
 
 caote_status caote_compact(void* K, void* V, float* base_score, const int32_t* kept_idx,
@@ -178,13 +203,13 @@ caote_status caote_compact(void* K, void* V, float* base_score, const int32_t* k
   st = check_ws(layout, budget, workspace, workspace_bytes, p);
   if (st != CAOTE_OK) return st;
   p.K = K; p.V = V; p.base = base_score; p.kept = const_cast<int32_t*>(kept_idx); p.mode = mode;
-  return device_status(caote::launch_compact(p, (hipStream_t)hip_stream), "compact");
+  return device_status(caote::launch_compact(p, (hipStream_t)hip_stream, nullptr), "compact");
 }
 
-caote_status caote_evict(const void* q_window, void* K, void* V, float* base_score,
-                         const caote_layout* layout, int32_t budget, int32_t mode, float* scores,
-                         int32_t* kept_idx, void* workspace, size_t workspace_bytes,
-                         void* hip_stream) {
+static caote_status evict_impl(const void* q_window, void* K, void* V, float* base_score,
+                               const caote_layout* layout, int32_t budget, int32_t mode,
+                               float* scores, int32_t* kept_idx, void* workspace,
+                               size_t workspace_bytes, hipStream_t s, caote::PhaseHook* hook) {
   caote_status st = check_layout(layout, budget, true);
   if (st != CAOTE_OK) return st;
   if (!q_window || !K || !V || !scores || !kept_idx)
@@ -199,12 +224,48 @@ caote_status caote_evict(const void* q_window, void* K, void* V, float* base_sco
   p.q = q_window; p.K = K; p.V = V; p.base = base_score; p.scores = scores; p.kept = kept_idx;
   p.mode = mode;
   if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
+  st = do_score(p, s, hook);
+  if (st != CAOTE_OK) return st;
+  st = device_status(caote::launch_select(p, s, hook), "select");
+  if (st != CAOTE_OK) return st;
+  return device_status(caote::launch_compact(p, s, hook), "compact");
+}
+
+caote_status caote_evict(const void* q_window, void* K, void* V, float* base_score,
+                         const caote_layout* layout, int32_t budget, int32_t mode, float* scores,
+                         int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  return evict_impl(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx, workspace,
+                    workspace_bytes, (hipStream_t)hip_stream, nullptr);
+}
+
+caote_status caote_evict_timed(const void* q_window, void* K, void* V, float* base_score,
+                               const caote_layout* layout, int32_t budget, int32_t mode,
+                               float* scores, int32_t* kept_idx, void* workspace,
+                               size_t workspace_bytes, void* hip_stream, float* phase_ms,
+                               int32_t* n_phases) {
+  if (!phase_ms || !n_phases) return fail(CAOTE_EINVAL, "phase_ms and n_phases must not be NULL");
   hipStream_t s = (hipStream_t)hip_stream;
-  st = do_score(p, s);
+  PhaseClock clock(s);
+  if (!clock.ok) return fail(CAOTE_EDEVICE, "could not create or record HIP events");
+  caote_status st = evict_impl(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx,
+                               workspace, workspace_bytes, s, &clock);
   if (st != CAOTE_OK) return st;
-  st = device_status(caote::launch_select(p, s), "select");
-  if (st != CAOTE_OK) return st;
-  return device_status(caote::launch_compact(p, s), "compact");
+  if (!clock.ok) return fail(CAOTE_EDEVICE, "hipEventRecord failed");
+  hipError_t e = hipEventSynchronize(clock.ev[clock.n]);
+  if (e != hipSuccess) return device_status(e, "hipEventSynchronize");
+  for (int i = 0; i < clock.n; ++i) {
+    e = hipEventElapsedTime(&phase_ms[i], clock.ev[i], clock.ev[i + 1]);
+    if (e != hipSuccess) return device_status(e, "hipEventElapsedTime");
+    g_phase_names[i] = clock.names[i];
+  }
+  for (int i = clock.n; i < CAOTE_MAX_PHASES; ++i) g_phase_names[i] = nullptr;
+  *n_phases = clock.n;
+  return CAOTE_OK;
+}
+
+const char* caote_phase_name(int32_t i) {
+  return i >= 0 && i < CAOTE_MAX_PHASES && g_phase_names[i] ? g_phase_names[i] : "";
 }
 
 }  // extern "C"

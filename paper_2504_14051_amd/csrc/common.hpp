@@ -79,9 +79,17 @@ __device__ __forceinline__ uint32_t float_key(float f) {
 }
 
 // ---- launchers (one per source file) --------------------------------------------
-hipError_t launch_score_generic(const Params& p, hipStream_t s);
-hipError_t launch_value_passes(const Params& p, hipStream_t s);
-hipError_t launch_select(const Params& p, hipStream_t s);
-hipError_t launch_compact(const Params& p, hipStream_t s);
+// A launcher calls hook->mark(name) after each kernel it enqueues (measurement aid).
+struct PhaseHook {
+  virtual void mark(const char* name) = 0;
+ protected:
+  ~PhaseHook() = default;
+};
+inline void mark(PhaseHook* h, const char* name) { if (h) h->mark(name); }
+
+hipError_t launch_score_generic(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook);
 
 }  // namespace caote

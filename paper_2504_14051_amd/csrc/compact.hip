@@ -68,12 +68,14 @@ __global__ __launch_bounds__(kThreads) void k_move_rows(const Params p, int row_
 
 }  // namespace
 
-hipError_t launch_compact(const Params& p, hipStream_t s) {
+hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int row_bytes = p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
   const int64_t chunks = (int64_t)p.budget * (row_bytes / 16);
   const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads), p.B * p.Hkv);
   hipLaunchKernelGGL(k_move_rows<0>, grid, dim3(kThreads), 0, s, p, row_bytes);
+  mark(hook, "compact_gather");
   hipLaunchKernelGGL(k_move_rows<1>, grid, dim3(kThreads), 0, s, p, row_bytes);
+  mark(hook, "compact_scatter");
   return hipGetLastError();
 }
 

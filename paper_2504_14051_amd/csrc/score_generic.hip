@@ -126,22 +126,25 @@ __global__ void k_merge_stats(const Params p) {
 }
 
 template <typename T, int D>
-hipError_t launch_t(const Params& p, hipStream_t s) {
+hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_split, p.B * p.Hkv);
   hipLaunchKernelGGL((k_logits_generic<T, D, 0>), grid, dim3(kThreads), 0, s, p);
+  mark(hook, "key_rowstats");
   hipLaunchKernelGGL(k_merge_stats, dim3((p.R + 63) / 64, p.B * p.Hkv), dim3(64), 0, s, p);
+  mark(hook, "merge_stats");
   hipLaunchKernelGGL((k_logits_generic<T, D, 1>), grid, dim3(kThreads),
                      (size_t)p.split_len * sizeof(float), s, p);
+  mark(hook, "key_colsum");
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_score_generic(const Params& p, hipStream_t s) {
+hipError_t launch_score_generic(const Params& p, hipStream_t s, PhaseHook* hook) {
   if (p.dtype == CAOTE_F32) {
-    return p.D == 64 ? launch_t<float, 64>(p, s) : launch_t<float, 128>(p, s);
+    return p.D == 64 ? launch_t<float, 64>(p, s, hook) : launch_t<float, 128>(p, s, hook);
   }
-  return p.D == 64 ? launch_t<bf16_t, 64>(p, s) : launch_t<bf16_t, 128>(p, s);
+  return p.D == 64 ? launch_t<bf16_t, 64>(p, s, hook) : launch_t<bf16_t, 128>(p, s, hook);
 }
 
 }  // namespace caote

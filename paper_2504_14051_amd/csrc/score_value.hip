@@ -123,20 +123,22 @@ __global__ __launch_bounds__(kThreads) void k_vscore(const Params p) {
 }
 
 template <typename T, int D>
-hipError_t launch_t(const Params& p, hipStream_t s) {
+hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_vchunk, p.B * p.Hkv);
   hipLaunchKernelGGL((k_vsum<T, D>), grid, dim3(kThreads), 0, s, p);
+  mark(hook, "value_sum");
   hipLaunchKernelGGL((k_vscore<T, D>), grid, dim3(kThreads), 0, s, p);
+  mark(hook, "value_score");
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_value_passes(const Params& p, hipStream_t s) {
+hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook) {
   if (p.dtype == CAOTE_F32) {
-    return p.D == 64 ? launch_t<float, 64>(p, s) : launch_t<float, 128>(p, s);
+    return p.D == 64 ? launch_t<float, 64>(p, s, hook) : launch_t<float, 128>(p, s, hook);
   }
-  return p.D == 64 ? launch_t<bf16_t, 64>(p, s) : launch_t<bf16_t, 128>(p, s);
+  return p.D == 64 ? launch_t<bf16_t, 64>(p, s, hook) : launch_t<bf16_t, 128>(p, s, hook);
 }
 
 }  // namespace caote

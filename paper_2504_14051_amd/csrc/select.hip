@@ -94,8 +94,9 @@ __global__ __launch_bounds__(kSelThreads) void k_select_single(const Params p) {
 
 }  // namespace
 
-hipError_t launch_select(const Params& p, hipStream_t s) {
+hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook) {
   hipLaunchKernelGGL(k_select_single, dim3(p.B * p.Hkv), dim3(kSelThreads), 0, s, p);
+  mark(hook, "select");
   return hipGetLastError();
 }
 
