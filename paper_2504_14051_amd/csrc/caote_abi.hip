@@ -75,15 +75,18 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.c2 = L->softmax_scale * 1.4426950408889634f;
 
   const int BH = p.B * p.Hkv;
-  const int target = 1024;                       // workgroups wanted per launch
-  int n_split = ceil_div(target, BH);
-  n_split = n_split < 1 ? 1 : n_split;
-  int split_len = (int)align_up((size_t)ceil_div(p.cap, n_split), 64);
-  split_len = split_len < 256 ? 256 : (split_len > 8192 ? 8192 : split_len);
-  p.split_len = split_len;
-  p.n_split = ceil_div(p.cap, split_len);
-  p.vchunk_len = split_len;
-  p.n_vchunk = p.n_split;
+  // Token chunk per workgroup: about `target` workgroups per launch, whole 64-key tiles.
+  auto chunk_len = [&](int target, int lo, int hi) {
+    int n = ceil_div(target, BH);
+    n = n < 1 ? 1 : n;
+    int len = (int)align_up((size_t)ceil_div(p.cap, n), 64);
+    return len < lo ? lo : (len > hi ? hi : len);
+  };
+  p.use_mfma = p.dtype == CAOTE_BF16 && p.D == 128 && p.R > 16;
+  p.split_len = p.use_mfma ? chunk_len(768, 128, 1 << 20) : chunk_len(1024, 256, 8192);
+  p.n_split = ceil_div(p.cap, p.split_len);
+  p.vchunk_len = chunk_len(1024, 256, 8192);
+  p.n_vchunk = ceil_div(p.cap, p.vchunk_len);
   p.Rp = (int)align_up((size_t)p.R, 32);
 
   size_t off = 0;
@@ -116,7 +119,8 @@ caote_status device_status(hipError_t e, const char* what) {
 }
 
 caote_status do_score(Params& p, hipStream_t s, caote::PhaseHook* hook = nullptr) {
-  hipError_t e = caote::launch_score_generic(p, s, hook);
+  hipError_t e = p.use_mfma ? caote::launch_score_mfma(p, s, hook)
+                            : caote::launch_score_generic(p, s, hook);
   if (e != hipSuccess) return device_status(e, "score (key sweeps)");
   return device_status(caote::launch_value_passes(p, s, hook), "score (value sweeps)");
 }

@@ -34,6 +34,7 @@ struct Params {
   uint32_t* sel;      // [BH][kSelWords]       selection scratch (threshold etc.)
   void* stage;        // compaction staging
   int n_split, split_len, Rp, n_vchunk, vchunk_len;
+  int use_mfma;       // key sweeps on the matrix cores (bf16, head_dim 128, R > 16)
 };
 
 // Per-(sequence, head) selection record written by the threshold search.
@@ -88,6 +89,7 @@ struct PhaseHook {
 inline void mark(PhaseHook* h, const char* name) { if (h) h->mark(name); }
 
 hipError_t launch_score_generic(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_score_mfma(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook);

@@ -1,0 +1,268 @@
+// Window attention over the key cache on the matrix cores: bf16, head_dim 128.
+//
+// Two sweeps over K (Sec. 2, attention of the window queries over the cache), as in the
+// vector-ALU path, but the R x N logits come from v_mfma_f32_32x32x16_bf16 tiles:
+//   sweep 1 (MODE 0)  S^T tile = K_tile (32 keys, M) x Q^T (32 query rows, N): a lane
+//                     then holds 16 keys of ONE query row, so the running (max, sum)
+//                     of the softmax is lane-local -- no cross-lane work per tile.
+//   sweep 2 (MODE 1)  S tile = Q (32 rows, M) x K_tile^T (32 keys, N): a lane holds 16
+//                     rows of ONE key, so the column sum a_j is lane-local.
+// The A and B operands of this instruction have the same register layout (lane l holds
+// row/column l%32, k = 8*(l/32)..+7), so the same Q registers and the same K reads from
+// LDS serve both sweeps.
+//
+// A workgroup is 4 waves arranged WR (row waves) x WK (key waves); every wave keeps RBW
+// 32-row blocks of Q in registers for the whole sweep.  K tiles of 64 keys go through a
+// double-buffered, XOR-swizzled LDS stage: global -> registers one tile ahead -> LDS.
+#include "common.hpp"
+
+namespace caote {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kThreads = 256;
+constexpr int kTN = 64;                 // keys per LDS tile
+constexpr int kD = 128;
+constexpr int kRowBytes = kD * 2;       // 256
+constexpr int kChunks = kRowBytes / 16; // 16-byte chunks per key row
+
+__device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ (row & 15)) << 4); }
+
+// Key index inside a 32x32 output tile for accumulator register i when keys are the M
+// dimension (sweep 1); also the row index when rows are the M dimension (sweep 2).
+__device__ __forceinline__ int m_of(int i, int lane) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
+
+template <int WR, int RBW, int MODE>
+__global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
+  constexpr int WK = 4 / WR;            // key waves
+  constexpr int KBW = (kTN / 32) / WK;  // 32-key blocks per wave per tile
+  constexpr int ROWS = WR * RBW * 32;   // query rows per row group
+  const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
+  const int N = seq_len(p, b);
+  const int c0 = blockIdx.x * p.split_len;
+  if (c0 >= N) return;
+  const int c1 = min(N, c0 + p.split_len);
+  const int ntiles = (c1 - c0 + kTN - 1) / kTN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / WK, kw = wave % WK;
+  const int P = p.wic ? N - p.W : N;    // keys below P are visible to every row
+
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][kTN * kRowBytes];
+  __shared__ float a_lds[2][WR][kTN];
+  __shared__ int iw_lds[ROWS];          // window position of each row of the group
+  __shared__ float st_lds[WK][ROWS][2];
+
+  const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.K) +
+                            ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * 2;
+  const int64_t krow = p.ksn * 2;
+  float* a_out = p.a + (int64_t)bh * p.cap;
+
+  for (int rg0 = 0; rg0 < p.R; rg0 += ROWS) {
+    // ---- per-row-group set-up: Q fragments, window positions, normalisers ----------
+    for (int i = tid; i < ROWS; i += kThreads) iw_lds[i] = (rg0 + i) < p.R ? (rg0 + i) % p.W : -1;
+    bf16x8 qf[RBW][8];
+    float lse[RBW][16];
+    float m_run[RBW], l_run[RBW];
+    int nvis_row[RBW];                  // MODE 0: visible-key count of this lane's row
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+      const int rbase = rg0 + (wr * RBW + rb) * 32;
+      const int r = rbase + (lane & 31);
+      m_run[rb] = -INFINITY; l_run[rb] = 0.f; nvis_row[rb] = 0;
+      if (r < p.R) {
+        const int g = r / p.W, iw = r % p.W;
+        const unsigned char* qp = reinterpret_cast<const unsigned char*>(p.q) +
+            ((int64_t)b * p.qsb + (int64_t)(hk * p.G + g) * p.qsh + (int64_t)iw * p.qsw) * 2 + (lane >> 5) * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+          qf[rb][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + ks * 32));
+        nvis_row[rb] = p.wic ? P + iw + 1 : N;
+      } else {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+      }
+      if (MODE == 1) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int rr = rbase + m_of(i, lane);
+          lse[rb][i] = rr < p.R ? p.lse2[(int64_t)bh * p.Rp + rr] : INFINITY;
+        }
+      }
+    }
+    // ---- sweep over the key tiles of this split --------------------------------------
+    uint4 pf[4];
+    auto gload = [&](int t) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int id = tid + u * kThreads, row = id / kChunks, ch = id % kChunks;
+        const int j = min(c0 + t * kTN + row, N - 1);      // rows past the end repeat the last one
+        pf[u] = *reinterpret_cast<const uint4*>(Kb + j * krow + ch * 16);
+      }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int id = tid + u * kThreads, row = id / kChunks, ch = id % kChunks;
+        *reinterpret_cast<uint4*>(&Ks[buf][swz(row, ch)]) = pf[u];
+      }
+    };
+    __syncthreads();                     // previous row group is done with LDS
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    for (int t = 0; t < ntiles; ++t) {
+      const int buf = t & 1;
+      const int tile0 = c0 + t * kTN;
+      if (t + 1 < ntiles) gload(t + 1);
+      const bool tail = tile0 + kTN > min(P, N);             // some element may be masked
+#pragma unroll
+      for (int kbi = 0; kbi < KBW; ++kbi) {
+        const int kb = kw * KBW + kbi;                        // 32-key block inside the tile
+        f32x16 acc[RBW];
+#pragma unroll
+        for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const int row = kb * 32 + (lane & 31);
+          const bf16x8 kf = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const uint4*>(&Ks[buf][swz(row, 2 * ks + (lane >> 5))]));
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb) {
+            if (MODE == 0) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], acc[rb], 0, 0, 0);
+            else           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf, acc[rb], 0, 0, 0);
+          }
+        }
+        const int jb = tile0 + kb * 32;                       // first key of the block
+        if (MODE == 0) {
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb) {
+            float t16[16];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              float tv = acc[rb][i] * p.c2;
+              if (tail && jb + m_of(i, lane) >= nvis_row[rb]) tv = -INFINITY;
+              t16[i] = tv;
+              mx = fmaxf(mx, tv);
+            }
+            const float mn = fmaxf(m_run[rb], mx);
+            if (mn > -INFINITY) {
+              float s = 0.f;
+#pragma unroll
+              for (int i = 0; i < 16; ++i) s += exp2f(t16[i] - mn);
+              l_run[rb] = l_run[rb] * exp2f(m_run[rb] - mn) + s;
+              m_run[rb] = mn;
+            }
+          }
+        } else {
+          float cs = 0.f;
+          const int j = jb + (lane & 31);
+#pragma unroll
+          for (int rb = 0; rb < RBW; ++rb) {
+            const int rl = (wr * RBW + rb) * 32;                // row offset inside the group
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              float pv = exp2f(acc[rb][i] * p.c2 - lse[rb][i]);
+              if (tail) {
+                const int iw = iw_lds[rl + m_of(i, lane)];
+                const bool vis = j < N && iw >= 0 && (!p.wic || j < P + iw + 1);
+                pv = vis ? pv : 0.f;
+              }
+              cs += pv;
+            }
+          }
+          cs += __shfl_xor(cs, 32, kWave);
+          if (lane < 32) a_lds[buf][wr][kb * 32 + lane] = cs;
+        }
+      }
+      if (t + 1 < ntiles) lstore(buf ^ 1);
+      __syncthreads();
+      if (MODE == 1 && tid < kTN && tile0 + tid < c1) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < WR; ++w) s += a_lds[buf][w][tid];
+        if (rg0 == 0) a_out[tile0 + tid] = s;
+        else a_out[tile0 + tid] += s;                          // later row groups add on
+      }
+    }
+    // ---- end of sweep 1: merge the two half-waves, then the key waves ------------------
+    if (MODE == 0) {
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        const float m2 = __shfl_xor(m_run[rb], 32, kWave), l2 = __shfl_xor(l_run[rb], 32, kWave);
+        const float M = fmaxf(m_run[rb], m2);
+        float L = 0.f;
+        if (m_run[rb] > -INFINITY) L += l_run[rb] * exp2f(m_run[rb] - M);
+        if (m2 > -INFINITY) L += l2 * exp2f(m2 - M);
+        if (lane < 32) {
+          const int rl = (wr * RBW + rb) * 32 + lane;
+          st_lds[kw][rl][0] = M; st_lds[kw][rl][1] = L;
+        }
+      }
+      __syncthreads();
+      for (int rl = tid; rl < ROWS; rl += kThreads) {
+        if (rg0 + rl >= p.R) continue;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < WK; ++w) M = fmaxf(M, st_lds[w][rl][0]);
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < WK; ++w)
+          if (st_lds[w][rl][0] > -INFINITY) L += st_lds[w][rl][1] * exp2f(st_lds[w][rl][0] - M);
+        float* st = p.stats + (((int64_t)bh * p.n_split + blockIdx.x) * p.Rp + rg0 + rl) * 2;
+        st[0] = M; st[1] = L;
+      }
+    }
+  }
+}
+
+// lse2_r = log2 sum_j exp2(t_rj): one wave per query row, lanes stride over the splits.
+__global__ __launch_bounds__(kThreads) void k_merge_stats_wave(const Params p) {
+  const int bh = blockIdx.y, b = bh / p.Hkv;
+  const int r = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (r >= p.R) return;
+  const int N = seq_len(p, b);
+  const int ns = (N + p.split_len - 1) / p.split_len;
+  const float* st = p.stats + ((int64_t)bh * p.n_split * p.Rp + r) * 2;
+  float M = -INFINITY;
+  for (int s = lane; s < ns; s += kWave) M = fmaxf(M, st[(int64_t)s * p.Rp * 2]);
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, kWave));
+  float L = 0.f;
+  for (int s = lane; s < ns; s += kWave) {
+    const float ms = st[(int64_t)s * p.Rp * 2];
+    if (ms > -INFINITY) L += st[(int64_t)s * p.Rp * 2 + 1] * exp2f(ms - M);
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) L += __shfl_xor(L, o, kWave);
+  if (lane == 0) p.lse2[(int64_t)bh * p.Rp + r] = L > 0.f ? M + log2f(L) : INFINITY;
+}
+
+template <int WR, int RBW>
+hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
+  const dim3 grid(p.n_split, p.B * p.Hkv);
+  hipLaunchKernelGGL((k_logits_mfma<WR, RBW, 0>), grid, dim3(kThreads), 0, s, p);
+  mark(hook, "key_rowstats");
+  hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kThreads), 0, s, p);
+  mark(hook, "merge_stats");
+  hipLaunchKernelGGL((k_logits_mfma<WR, RBW, 1>), grid, dim3(kThreads), 0, s, p);
+  mark(hook, "key_colsum");
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Requires: bf16, head_dim 128, split_len a multiple of 64.
+hipError_t launch_score_mfma(const Params& p, hipStream_t s, PhaseHook* hook) {
+  const int nrb = (p.R + 31) / 32;
+  if (nrb <= 2) return launch_cfg<2, 1>(p, s, hook);
+  if (nrb <= 4) return launch_cfg<2, 2>(p, s, hook);
+  return launch_cfg<4, 2>(p, s, hook);
+}
+
+}  // namespace caote

@@ -135,6 +135,10 @@ def test_decode_stream_steps(B, oracle):
     dict(n_q_heads=14, n_kv_heads=2, window=5),                   # G = 7, R = 35
     dict(window=1, n_q_heads=2, n_kv_heads=2, base=synth.BASE_NONE),   # TOVA
     dict(window_in_cache=0),
+    dict(window=40),                                              # R = 160: padded row blocks
+    dict(window=80, base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=80),   # R = 320: two row groups
+    dict(window=16, n_q_heads=2, n_kv_heads=2),                   # R = 16: vector-ALU path, bf16
+    dict(window=17, n_q_heads=2, n_kv_heads=2),                   # R = 17: smallest matrix-core case
 ], ids=lambda kw: "-".join(f"{k}={v}" for k, v in kw.items()) or "h2o")
 def test_small_shapes_ragged(B, oracle, kw):
     wl = small(**kw)
