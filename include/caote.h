@@ -85,7 +85,7 @@ typedef struct caote_layout {
   int64_t q_stride_b, q_stride_h, q_stride_w;     /* all multiples of 16 bytes        */
   int32_t dtype;             /* caote_dtype of q_window, K, V                         */
   int32_t base;              /* caote_base                                            */
-  float   softmax_scale;     /* multiplies every logit; the paper leaves out the
+  float   softmax_scale;     /* > 0; multiplies every logit; the paper leaves out the
                                 usual 1/sqrt(head_dim), the caller supplies it        */
   int32_t pool_kernel;       /* odd, >= 1; used by CAOTE_BASE_SNAPKV only             */
   int32_t window_in_cache;   /* 1: the last W rows of K/V are the window's own

@@ -43,6 +43,7 @@ caote_status check_layout(const caote_layout* L, int32_t budget, bool need_budge
   if (L->n_protect_head < 0 || L->n_protect_tail < 0) return fail(CAOTE_EINVAL, "negative protected row count");
   if (!(L->softmax_scale == L->softmax_scale) || isinf(L->softmax_scale))
     return fail(CAOTE_EINVAL, "softmax_scale is not finite");
+  if (!(L->softmax_scale > 0.f)) return fail(CAOTE_EINVAL, "softmax_scale must be > 0");
   if (L->window_in_cache && !L->seq_lens && L->capacity < L->window)
     return fail(CAOTE_EINVAL, "window (%d) exceeds the cache length (%d)", L->window, L->capacity);
   const int esz = L->dtype == CAOTE_F32 ? 4 : 2;

@@ -14,6 +14,8 @@
 // A workgroup is 4 waves arranged WR (row waves) x WK (key waves); every wave keeps RBW
 // 32-row blocks of Q in registers for the whole sweep.  K tiles of 64 keys go through a
 // double-buffered, XOR-swizzled LDS stage: global -> registers one tile ahead -> LDS.
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace caote {
@@ -92,69 +94,64 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
       }
     }
     // ---- sweep over the key tiles of this split --------------------------------------
-    uint4 pf[4];
-    auto gload = [&](int t) {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
+    // Global loads run two tiles ahead of the math (two register sets), LDS is double
+    // buffered: tile t+2 is fetched while tile t is computed and lands in the LDS buffer
+    // that tile t used, one barrier later.
+    struct Fetch { uint4 u0, u1, u2, u3; };                 // one thread's share of a tile
+    auto gload = [&](int t) -> Fetch {
+      auto one = [&](int u) -> uint4 {
         const int id = tid + u * kThreads, row = id / kChunks, ch = id % kChunks;
         const int j = min(c0 + t * kTN + row, N - 1);      // rows past the end repeat the last one
-        pf[u] = *reinterpret_cast<const uint4*>(Kb + j * krow + ch * 16);
-      }
+        return *reinterpret_cast<const uint4*>(Kb + j * krow + ch * 16);
+      };
+      return Fetch{one(0), one(1), one(2), one(3)};
     };
-    auto lstore = [&](int buf) {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
+    auto lstore = [&](int buf, const Fetch f) {
+      auto one = [&](int u, const uint4 v) {
         const int id = tid + u * kThreads, row = id / kChunks, ch = id % kChunks;
-        *reinterpret_cast<uint4*>(&Ks[buf][swz(row, ch)]) = pf[u];
-      }
+        *reinterpret_cast<uint4*>(&Ks[buf][swz(row, ch)]) = v;
+      };
+      one(0, f.u0); one(1, f.u1); one(2, f.u2); one(3, f.u3);
     };
-    __syncthreads();                     // previous row group is done with LDS
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-      const int buf = t & 1;
-      const int tile0 = c0 + t * kTN;
-      if (t + 1 < ntiles) gload(t + 1);
-      const bool tail = tile0 + kTN > min(P, N);             // some element may be masked
+    // One 64-key tile out of LDS buffer `buf`.  TAIL: some logits of the tile are masked
+    // (keys past the end of the cache, or window keys a row must not see).
+    auto tile = [&](auto tail_tag, int buf, int tile0) {
+      constexpr bool TAIL = decltype(tail_tag)::value;
 #pragma unroll
       for (int kbi = 0; kbi < KBW; ++kbi) {
         const int kb = kw * KBW + kbi;                        // 32-key block inside the tile
+        const int row = kb * 32 + (lane & 31);
         f32x16 acc[RBW];
 #pragma unroll
-        for (int rb = 0; rb < RBW; ++rb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) acc[rb][i] = 0.f;
-#pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-          const int row = kb * 32 + (lane & 31);
           const bf16x8 kf = __builtin_bit_cast(
               bf16x8, *reinterpret_cast<const uint4*>(&Ks[buf][swz(row, 2 * ks + (lane >> 5))]));
 #pragma unroll
           for (int rb = 0; rb < RBW; ++rb) {
-            if (MODE == 0) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], acc[rb], 0, 0, 0);
-            else           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf, acc[rb], 0, 0, 0);
+            const f32x16 cin = ks == 0 ? f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
+                                                0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f} : acc[rb];
+            if (MODE == 0) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], cin, 0, 0, 0);
+            else           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf, cin, 0, 0, 0);
           }
         }
         const int jb = tile0 + kb * 32;                       // first key of the block
         if (MODE == 0) {
 #pragma unroll
           for (int rb = 0; rb < RBW; ++rb) {
-            float t16[16];
-            float mx = -INFINITY;
+            if (TAIL) {                                         // masked logits become -inf
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              float tv = acc[rb][i] * p.c2;
-              if (tail && jb + m_of(i, lane) >= nvis_row[rb]) tv = -INFINITY;
-              t16[i] = tv;
-              mx = fmaxf(mx, tv);
+              for (int i = 0; i < 16; ++i)
+                if (jb + m_of(i, lane) >= nvis_row[rb]) acc[rb][i] = -INFINITY;
             }
-            const float mn = fmaxf(m_run[rb], mx);
-            if (mn > -INFINITY) {
+            float mx = acc[rb][0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = __builtin_fmaxf(mx, acc[rb][i]);
+            const float mn = __builtin_fmaxf(m_run[rb], mx * p.c2);     // c2 > 0
+            if (!TAIL || mn > -INFINITY) {
               float s = 0.f;
 #pragma unroll
-              for (int i = 0; i < 16; ++i) s += exp2f(t16[i] - mn);
-              l_run[rb] = l_run[rb] * exp2f(m_run[rb] - mn) + s;
+              for (int i = 0; i < 16; ++i) s += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[rb][i], p.c2, -mn));
+              l_run[rb] = l_run[rb] * __builtin_amdgcn_exp2f(m_run[rb] - mn) + s;
               m_run[rb] = mn;
             }
           }
@@ -166,8 +163,8 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
             const int rl = (wr * RBW + rb) * 32;                // row offset inside the group
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-              float pv = exp2f(acc[rb][i] * p.c2 - lse[rb][i]);
-              if (tail) {
+              float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[rb][i], p.c2, -lse[rb][i]));
+              if (TAIL) {
                 const int iw = iw_lds[rl + m_of(i, lane)];
                 const bool vis = j < N && iw >= 0 && (!p.wic || j < P + iw + 1);
                 pv = vis ? pv : 0.f;
@@ -179,14 +176,42 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
           if (lane < 32) a_lds[buf][wr][kb * 32 + lane] = cs;
         }
       }
-      if (t + 1 < ntiles) lstore(buf ^ 1);
-      __syncthreads();
+    };
+    auto math = [&](int t, int buf) {
+      const int tile0 = c0 + t * kTN;
+      if (tile0 + kTN > min(P, N)) tile(std::true_type{}, buf, tile0);
+      else                         tile(std::false_type{}, buf, tile0);
+    };
+    auto flush_a = [&](int t, int buf) {                     // after the barrier of step t
+      const int tile0 = c0 + t * kTN;
       if (MODE == 1 && tid < kTN && tile0 + tid < c1) {
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < WR; ++w) s += a_lds[buf][w][tid];
         if (rg0 == 0) a_out[tile0 + tid] = s;
         else a_out[tile0 + tid] += s;                          // later row groups add on
+      }
+    };
+    // Loop step t: fetch tile t+2 into the register set that tile t came from, do the math
+    // of tile t, move tile t+1 from its registers into the other LDS buffer.  The two
+    // register sets are separate named values, so the loads stay in flight across the math.
+    __syncthreads();                     // previous row group is done with LDS
+    Fetch fa = gload(0), fb = fa;
+    if (ntiles > 1) fb = gload(1);
+    lstore(0, fa);
+    __syncthreads();
+    for (int t = 0; t < ntiles; t += 2) {
+      if (t + 2 < ntiles) fa = gload(t + 2);
+      math(t, 0);
+      if (t + 1 < ntiles) lstore(1, fb);
+      __syncthreads();
+      flush_a(t, 0);
+      if (t + 1 < ntiles) {
+        if (t + 3 < ntiles) fb = gload(t + 3);
+        math(t + 1, 1);
+        if (t + 2 < ntiles) lstore(0, fa);
+        __syncthreads();
+        flush_a(t + 1, 1);
       }
     }
     // ---- end of sweep 1: merge the two half-waves, then the key waves ------------------
