@@ -74,6 +74,7 @@ def main():
     ap.add_argument("--workload", default="llama3-8b-32k")
     ap.add_argument("--layers", type=int, default=16, help="independent layer buffers to rotate over")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (each (sequence, layer, KV head) is "
@@ -118,14 +119,40 @@ def main():
         q, K, V, base = layers[i % n_layers]
         B.caote_evict(q, K, V, base, L, wl.budget, mode, scores, kept, ws, stream)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    if args.no_graph:
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    else:
+        # The library neither allocates nor synchronises, so the K steps are captured once
+        # into a HIP graph (launch-bound otherwise: ten short kernels per step) and replayed.
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            stream = side
+            for i in range(3):
+                step(i)
+            side.synchronize()
+            g_warm, g_timed = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_warm, stream=side):
+                for i in range(args.warmup):
+                    step(i)
+            with torch.cuda.graph(g_timed, stream=side):
+                for i in range(args.steps):
+                    step(args.warmup + i)
+            if args.warmup:
+                g_warm.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            g_timed.replay()
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+        stream = torch.cuda.current_stream()
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = wl.batch * wl.context / (dt / args.steps)
 
@@ -154,7 +181,8 @@ def main():
                    "head_dim": wl.head_dim, "context": wl.context, "window": wl.window,
                    "budget": wl.budget, "base": {0: "none", 1: "h2o", 2: "snapkv"}[wl.base],
                    "pool_kernel": wl.pool_kernel, "batch": wl.batch, "layer_buffers": n_layers,
-                   "entry_point": "caote_evict"},
+                   "entry_point": "caote_evict",
+                   "launch": "stream" if args.no_graph else "hip_graph"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch": dom_bytes, "ms_per_launch": phases[dom]},

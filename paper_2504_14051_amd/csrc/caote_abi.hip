@@ -86,7 +86,7 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.use_mfma = p.dtype == CAOTE_BF16 && p.D == 128 && p.R > 16;
   p.split_len = p.use_mfma ? chunk_len(768, 128, 1 << 20) : chunk_len(1024, 256, 8192);
   p.n_split = ceil_div(p.cap, p.split_len);
-  p.vchunk_len = chunk_len(1024, 256, 8192);
+  p.vchunk_len = caote::kVChunk;
   p.n_vchunk = ceil_div(p.cap, p.vchunk_len);
   p.Rp = (int)align_up((size_t)p.R, 32);
 
@@ -98,7 +98,8 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.h = (float*)carve((size_t)BH * p.cap * sizeof(float));
   p.opart = (float*)carve((size_t)BH * p.n_vchunk * p.D * sizeof(float));
   p.zpart = (float*)carve((size_t)BH * p.n_vchunk * sizeof(float));
-  p.sel = (uint32_t*)carve((size_t)BH * caote::kSelWords * sizeof(uint32_t));
+  p.osum = (float*)carve((size_t)BH * (caote::kMaxD + 1) * sizeof(float));
+  p.hist = (uint32_t*)carve((size_t)BH * caote::kHistBins * sizeof(uint32_t));
   const size_t row_bytes = (size_t)p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
   const int bud = budget > 0 ? budget : 0;
   p.stage = carve((size_t)BH * bud * (2 * row_bytes + sizeof(float)));
@@ -228,6 +229,7 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
   if (st != CAOTE_OK) return st;
   p.q = q_window; p.K = K; p.V = V; p.base = base_score; p.scores = scores; p.kept = kept_idx;
   p.mode = mode;
+  p.hist_zeroed = 1;
   if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
   st = do_score(p, s, hook);
   if (st != CAOTE_OK) return st;

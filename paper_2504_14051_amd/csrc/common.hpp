@@ -9,6 +9,10 @@
 namespace caote {
 
 constexpr int kWave = 64;
+constexpr int kVChunk = 256;      // tokens per workgroup in the value sweeps
+constexpr int kMaxD = 128;        // largest head_dim
+constexpr int kHistBins = 4096;   // selection histogram: top 12 bits of the score key
+constexpr int kHistShift = 20;
 
 // Everything a kernel needs to know about one call.  Passed by value.
 struct Params {
@@ -31,14 +35,13 @@ struct Params {
   float* h;           // [BH][cap]             base score (aliases `base` for H2O)
   float* opart;       // [BH][n_vchunk][D]     partial sum of h_j v_j
   float* zpart;       // [BH][n_vchunk]        partial sum of h_j
-  uint32_t* sel;      // [BH][kSelWords]       selection scratch (threshold etc.)
+  float* osum;        // [BH][kMaxD+1]         sum h_j v_j (un-normalised) and, last, Z
+  uint32_t* hist;     // [BH][kHistBins]       histogram of the score keys
+  int hist_zeroed;    // an earlier kernel of this call has cleared `hist` (fused call)
   void* stage;        // compaction staging
   int n_split, split_len, Rp, n_vchunk, vchunk_len;
   int use_mfma;       // key sweeps on the matrix cores (bf16, head_dim 128, R > 16)
 };
-
-// Per-(sequence, head) selection record written by the threshold search.
-constexpr int kSelWords = 8;   // [0] threshold key, [1] #ties to keep, [2] n_keep
 
 __device__ __forceinline__ int seq_len(const Params& p, int b) {
   if (p.seq_lens == nullptr) return p.cap;
@@ -71,6 +74,12 @@ __device__ __forceinline__ float team_sum(float v) {
 #pragma unroll
   for (int m = TL / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
   return v;
+}
+
+// Clears the per-head counters that later kernels of the same call accumulate into.
+// Called by one workgroup per head of a kernel that runs before them.
+__device__ __forceinline__ void reset_counters(const Params& p, int bh) {
+  for (int i = threadIdx.x; i < kHistBins; i += blockDim.x) p.hist[(int64_t)bh * kHistBins + i] = 0u;
 }
 
 // Order-preserving map float -> uint32 (larger float <=> larger key).

@@ -109,6 +109,7 @@ __global__ __launch_bounds__(kThreads) void k_logits_generic(const Params p) {
 // lse2_r = log2 sum_j exp2(t_rj), merged over the key splits that hold tokens.
 __global__ void k_merge_stats(const Params p) {
   const int bh = blockIdx.y, b = bh / p.Hkv;
+  if (blockIdx.x == 0) reset_counters(p, bh);
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= p.R) return;
   const int N = seq_len(p, b);

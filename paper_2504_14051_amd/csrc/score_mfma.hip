@@ -248,6 +248,7 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
 // lse2_r = log2 sum_j exp2(t_rj): one wave per query row, lanes stride over the splits.
 __global__ __launch_bounds__(kThreads) void k_merge_stats_wave(const Params p) {
   const int bh = blockIdx.y, b = bh / p.Hkv;
+  if (blockIdx.x == 0) reset_counters(p, bh);
   const int r = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (r >= p.R) return;

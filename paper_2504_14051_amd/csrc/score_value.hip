@@ -1,11 +1,15 @@
 // Value-side sweeps of the CAOTE score (Sec. 3.2 general form, Sec. 3.3 FastCAOTE).
 //
 //   k_vsum   : base score h from the column sums a (H2O accumulate / SnapKV max-pool),
-//              then partial sums  sum_j h_j v_j  and  sum_j h_j  per chunk of tokens.
+//              then partial sums  sum_j h_j v_j  and  sum_j h_j  per chunk of 256 tokens.
+//   k_vfinal : adds the partials of a head up in chunk order (fixed order: the result
+//              does not depend on scheduling).
 //   k_vscore : o = (sum h_j v_j) / Z,  score_j = h_j / (Z - h_j) * ||v_j - o||_2.
 //
 // ||v_j - o|| is taken directly on the differences (not via ||v||^2 - 2 v.o + ||o||^2,
 // which cancels when v_j is close to o).  1 - w_j is formed as (Z - h_j) / Z.
+// Both kernels are HBM-bound streams over V: every thread keeps 8 independent 16-byte
+// loads in flight, 16 lanes per 256-byte row.
 #include <float.h>
 
 #include "common.hpp"
@@ -14,55 +18,145 @@ namespace caote {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kUnroll = 8;
+constexpr int kFinalThreads = 1024;
+
+template <typename T> struct Frag;
+template <> struct Frag<bf16_t> { uint4 u; };
+template <> struct Frag<float> { float4 lo, hi; };
+
+__device__ __forceinline__ void fetch(const bf16_t* ptr, Frag<bf16_t>& f) { f.u = *reinterpret_cast<const uint4*>(ptr); }
+__device__ __forceinline__ void fetch(const float* ptr, Frag<float>& f) {
+  f.lo = *reinterpret_cast<const float4*>(ptr);
+  f.hi = *reinterpret_cast<const float4*>(ptr + 4);
+}
+__device__ __forceinline__ void zero(Frag<bf16_t>& f) { f.u = make_uint4(0, 0, 0, 0); }
+__device__ __forceinline__ void zero(Frag<float>& f) { f.lo = make_float4(0, 0, 0, 0); f.hi = f.lo; }
+__device__ __forceinline__ void widen(const Frag<bf16_t>& f, float (&x)[8]) {
+  x[0] = __uint_as_float(f.u.x << 16); x[1] = __uint_as_float(f.u.x & 0xffff0000u);
+  x[2] = __uint_as_float(f.u.y << 16); x[3] = __uint_as_float(f.u.y & 0xffff0000u);
+  x[4] = __uint_as_float(f.u.z << 16); x[5] = __uint_as_float(f.u.z & 0xffff0000u);
+  x[6] = __uint_as_float(f.u.w << 16); x[7] = __uint_as_float(f.u.w & 0xffff0000u);
+}
+__device__ __forceinline__ void widen(const Frag<float>& f, float (&x)[8]) {
+  x[0] = f.lo.x; x[1] = f.lo.y; x[2] = f.lo.z; x[3] = f.lo.w;
+  x[4] = f.hi.x; x[5] = f.hi.y; x[6] = f.hi.z; x[7] = f.hi.w;
+}
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
   constexpr int TL = D / 8;
   constexpr int RPI = kThreads / TL;      // rows in flight per iteration
+  constexpr int ITER = kVChunk / RPI;     // iterations per chunk
+  static_assert(ITER % kUnroll == 0, "chunk must be a whole number of unrolled groups");
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
-  const int c0 = blockIdx.x * p.vchunk_len;
+  const int c0 = blockIdx.x * kVChunk;
   if (c0 >= N) return;
-  const int c1 = min(N, c0 + p.vchunk_len);
-  const int team = threadIdx.x / TL, tl = threadIdx.x % TL;
+  const int tid = threadIdx.x, team = tid / TL, tl = tid % TL;
   const int lo = min(p.ph, N), hi = max(lo, N - p.pt);   // scored rows [lo,hi)
   const int half = p.pool / 2;
 
-  const float* a = p.a + (int64_t)bh * p.cap;
-  float* h = p.h + (int64_t)bh * p.cap;
-  const T* Vb = reinterpret_cast<const T*>(p.V) + (int64_t)b * p.vsb + (int64_t)hk * p.vsh + tl * 8;
+  __shared__ float w_lds[kVChunk];        // weight of each row of the chunk in sum h_j v_j
+  __shared__ float red[RPI][D];
+  __shared__ float zred[kThreads / kWave];
 
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  float zacc = 0.f;
-  for (int j = c0 + team; j < c1; j += RPI) {
-    const bool scored = j >= lo && j < hi;
-    float hj = a[j];
-    if (p.base_mode == CAOTE_BASE_H2O) {
-      hj += h[j];                           // h aliases the accumulator
-    } else if (p.base_mode == CAOTE_BASE_SNAPKV && scored) {
-      const int t0 = max(lo, j - half), t1 = min(hi - 1, j + half);
-      for (int t = t0; t <= t1; ++t) hj = fmaxf(hj, a[t]);
+  // ---- phase A: one thread per token: base score h_j --------------------------------
+  {
+    const float* a = p.a + (int64_t)bh * p.cap;
+    float* h = p.h + (int64_t)bh * p.cap;
+    const int j = c0 + tid;
+    float hj = 0.f;
+    bool scored = false;
+    if (j < N) {
+      scored = j >= lo && j < hi;
+      hj = a[j];
+      if (p.base_mode == CAOTE_BASE_H2O) {
+        hj += h[j];                           // h aliases the accumulator
+      } else if (p.base_mode == CAOTE_BASE_SNAPKV && scored) {
+        const int t0 = max(lo, j - half), t1 = min(hi - 1, j + half);
+        for (int t = t0; t <= t1; ++t) hj = fmaxf(hj, a[t]);
+      }
+      h[j] = hj;
     }
-    if (tl == 0) h[j] = hj;
-    if (scored) {
-      float vf[8];
-      load8(Vb + (int64_t)j * p.vsn, vf);
-      const float wgt = p.variant == CAOTE_FAST ? 1.f : hj;
+    w_lds[tid] = scored ? (p.variant == CAOTE_FAST ? 1.f : hj) : 0.f;
+    float z = scored ? hj : 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = fmaf(wgt, vf[e], acc[e]);
-      zacc += hj;
+    for (int o = 32; o >= 1; o >>= 1) z += __shfl_xor(z, o, kWave);
+    if ((tid & 63) == 0) zred[tid >> 6] = z;
+  }
+  __syncthreads();
+
+  // ---- phase B: stream the chunk of V -------------------------------------------------
+  const T* Vb = reinterpret_cast<const T*>(p.V) + (int64_t)b * p.vsb + (int64_t)hk * p.vsh + tl * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int it0 = 0; it0 < ITER; it0 += kUnroll) {
+    Frag<T> f[kUnroll];
+    float w[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int rl = (it0 + u) * RPI + team;
+      w[u] = w_lds[rl];
+      if (w[u] != 0.f) fetch(Vb + (int64_t)(c0 + rl) * p.vsn, f[u]); else zero(f[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      float x[8];
+      widen(f[u], x);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = fmaf(w[u], x[e], acc[e]);
     }
   }
-  __shared__ float red[RPI][D + 1];
 #pragma unroll
   for (int e = 0; e < 8; ++e) red[team][tl * 8 + e] = acc[e];
-  if (tl == 0) red[team][D] = zacc;
   __syncthreads();
-  if (threadIdx.x <= D) {
+  if (tid < D) {
     float s = 0.f;
-    for (int t = 0; t < RPI; ++t) s += red[t][threadIdx.x];
-    if (threadIdx.x < D) p.opart[((int64_t)bh * p.n_vchunk + blockIdx.x) * D + threadIdx.x] = s;
-    else p.zpart[(int64_t)bh * p.n_vchunk + blockIdx.x] = s;
+#pragma unroll
+    for (int t = 0; t < RPI; ++t) s += red[t][tid];
+    p.opart[((int64_t)bh * p.n_vchunk + blockIdx.x) * D + tid] = s;
+  } else if (tid == D) {
+    float z = 0.f;
+#pragma unroll
+    for (int w = 0; w < kThreads / kWave; ++w) z += zred[w];
+    p.zpart[(int64_t)bh * p.n_vchunk + blockIdx.x] = z;
+  }
+}
+
+// Adds the per-chunk partial sums of one head up, in chunk order.
+__global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
+  const int bh = blockIdx.x, b = bh / p.Hkv;
+  const int N = seq_len(p, b);
+  const int nch = (N + kVChunk - 1) / kVChunk;
+  const int tid = threadIdx.x, D = p.D;
+  // kFinalThreads / 128 chunk groups x 128 columns; group g takes chunks g, g+G, ...
+  constexpr int G = kFinalThreads / kMaxD;
+  const int g = tid / kMaxD, col = tid % kMaxD;
+  __shared__ float red[G][kMaxD + 1];
+  float s = 0.f, z = 0.f;
+  if (col < D) {
+    const float* op = p.opart + (int64_t)bh * p.n_vchunk * D + col;
+    int c = g;
+    for (; c + 3 * G < nch; c += 4 * G) {                     // four independent loads in flight
+      const float x0 = op[(int64_t)c * D], x1 = op[(int64_t)(c + G) * D];
+      const float x2 = op[(int64_t)(c + 2 * G) * D], x3 = op[(int64_t)(c + 3 * G) * D];
+      s += x0; s += x1; s += x2; s += x3;
+    }
+    for (; c < nch; c += G) s += op[(int64_t)c * D];
+  }
+  if (col == 0) {
+    const float* zp = p.zpart + (int64_t)bh * p.n_vchunk;
+    for (int c = g; c < nch; c += G) z += zp[c];
+    red[g][kMaxD] = z;
+  }
+  red[g][col] = s;
+  __syncthreads();
+  if (tid <= kMaxD) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < G; ++i) t += red[i][tid];
+    p.osum[(int64_t)bh * (kMaxD + 1) + tid] = t;
   }
 }
 
@@ -70,56 +164,55 @@ template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void k_vscore(const Params p) {
   constexpr int TL = D / 8;
   constexpr int RPI = kThreads / TL;
+  constexpr int ITER = kVChunk / RPI;
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
-  const int c0 = blockIdx.x * p.vchunk_len;
+  const int c0 = blockIdx.x * kVChunk;
   if (c0 >= N) return;
-  const int c1 = min(N, c0 + p.vchunk_len);
-  const int team = threadIdx.x / TL, tl = threadIdx.x % TL;
+  const int tid = threadIdx.x, team = tid / TL, tl = tid % TL;
   const int lo = min(p.ph, N), hi = max(lo, N - p.pt);
   const int n_scored = hi - lo;
-  const int nch = (N + p.vchunk_len - 1) / p.vchunk_len;
 
-  __shared__ float o_lds[D];
-  __shared__ float z_lds;
-  if (threadIdx.x <= D) {
-    float s = 0.f;
-    if (threadIdx.x < D) {
-      const float* op = p.opart + (int64_t)bh * p.n_vchunk * D + threadIdx.x;
-      for (int cidx = 0; cidx < nch; ++cidx) s += op[(int64_t)cidx * D];
-      o_lds[threadIdx.x] = s;
-    } else {
-      const float* zp = p.zpart + (int64_t)bh * p.n_vchunk;
-      for (int cidx = 0; cidx < nch; ++cidx) s += zp[cidx];
-      z_lds = s;
-    }
-  }
-  __syncthreads();
-  const float Z = z_lds;
+  __shared__ float d_lds[kVChunk];        // ||v_j - o|| of each row of the chunk
+
+  const float* os = p.osum + (int64_t)bh * (kMaxD + 1);
+  const float Z = os[kMaxD];
   const float onorm = p.variant == CAOTE_FAST ? 1.f / (float)max(n_scored, 1)
                                               : (Z > 0.f ? 1.f / Z : 0.f);
   float of[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) of[e] = o_lds[tl * 8 + e] * onorm;
+  for (int e = 0; e < 8; ++e) of[e] = os[tl * 8 + e] * onorm;
 
-  const float* h = p.h + (int64_t)bh * p.cap;
-  float* sc = p.scores + (int64_t)bh * p.cap;
   const T* Vb = reinterpret_cast<const T*>(p.V) + (int64_t)b * p.vsb + (int64_t)hk * p.vsh + tl * 8;
-  for (int j = c0 + team; j < c1; j += RPI) {
-    const bool scored = j >= lo && j < hi && n_scored > 1;
-    float out = INFINITY;
-    if (scored) {                           // uniform within the team
-      float vf[8];
-      load8(Vb + (int64_t)j * p.vsn, vf);
+#pragma unroll
+  for (int it0 = 0; it0 < ITER; it0 += kUnroll) {
+    Frag<T> f[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int j = c0 + (it0 + u) * RPI + team;
+      if (j >= lo && j < hi) fetch(Vb + (int64_t)j * p.vsn, f[u]); else zero(f[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      float x[8];
+      widen(f[u], x);
       float d2 = 0.f;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { const float t = vf[e] - of[e]; d2 = fmaf(t, t, d2); }
+      for (int e = 0; e < 8; ++e) { const float t = x[e] - of[e]; d2 = fmaf(t, t, d2); }
       d2 = team_sum<TL>(d2);
-      const float hj = h[j];
-      out = Z > 0.f ? hj / fmaxf(Z - hj, FLT_MIN) * sqrtf(d2) : 0.f;
+      if (tl == 0) d_lds[(it0 + u) * RPI + team] = sqrtf(d2);
     }
-    if (tl == 0) sc[j] = out;
   }
+  __syncthreads();
+  // ---- one thread per token: the score, and its histogram bin ---------------------------
+  const int j = c0 + tid;
+  if (j >= N) return;
+  float out = INFINITY;
+  if (j >= lo && j < hi && n_scored > 1) {
+    const float hj = p.h[(int64_t)bh * p.cap + j];
+    out = Z > 0.f ? hj / fmaxf(Z - hj, FLT_MIN) * d_lds[tid] : 0.f;
+  }
+  p.scores[(int64_t)bh * p.cap + j] = out;
 }
 
 template <typename T, int D>
@@ -127,6 +220,8 @@ hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_vchunk, p.B * p.Hkv);
   hipLaunchKernelGGL((k_vsum<T, D>), grid, dim3(kThreads), 0, s, p);
   mark(hook, "value_sum");
+  hipLaunchKernelGGL(k_vfinal, dim3(p.B * p.Hkv), dim3(kFinalThreads), 0, s, p);
+  mark(hook, "value_final");
   hipLaunchKernelGGL((k_vscore<T, D>), grid, dim3(kThreads), 0, s, p);
   mark(hook, "value_score");
   return hipGetLastError();

@@ -1,10 +1,14 @@
 // Per-head top-`budget` selection (Sec. 2: the top-b tokens by score are retained).
 //
-// The k-th largest score is found by a most-significant-digit radix search on the
-// order-preserving integer image of the floats (4 digits of 8 bits), then the kept
-// indices are emitted in ascending order with a block-wide prefix scan.  Equal scores
-// at the threshold keep the lower indices.  Integer work throughout: the result is
-// exact and independent of launch shape.
+// Scores are compared through their order-preserving 32-bit integer image, so the whole
+// selection is integer work: exact, and independent of launch shape.
+//   1. a 4096-bin histogram of the top 12 key bits per head (k_select_hist);
+//   2. one workgroup per head walks the histogram from the top to the bin that holds the
+//      budget-th largest score, gathers that bin's keys into LDS and finishes the radix
+//      search on the remaining 20 bits there (three short passes);
+//   3. the same workgroup emits the kept indices in ascending order: every wave owns a
+//      contiguous span of the tokens and places its survivors by ballot and popcount.
+// Equal scores at the threshold keep the lower indices.
 #include "common.hpp"
 
 namespace caote {
@@ -12,14 +16,19 @@ namespace {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
+constexpr int kCandMax = 12288;          // keys of the threshold bin held in LDS
 
-// Exclusive prefix count of `flag` over the block, plus the block total.
-__device__ __forceinline__ int block_excl_count(bool flag, int* wave_tot, int& total) {
-  const uint64_t bal = __ballot(flag);
+// Exclusive prefix sum of v over the block (threads in order) and the block total.
+__device__ __forceinline__ int block_excl_scan(int v, int* wave_tot, int& total) {
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-  const int in_wave = __popcll(bal & ((1ull << lane) - 1ull));
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int up = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += up;
+  }
   __syncthreads();                       // wave_tot is reused by consecutive calls
-  if (lane == 0) wave_tot[wv] = __popcll(bal);
+  if (lane == kWave - 1) wave_tot[wv] = inc;
   __syncthreads();
   int before = 0, tot = 0;
 #pragma unroll
@@ -29,45 +38,130 @@ __device__ __forceinline__ int block_excl_count(bool flag, int* wave_tot, int& t
     tot += t;
   }
   total = tot;
-  return before + in_wave;
+  return before + inc - v;
 }
 
-__global__ __launch_bounds__(kSelThreads) void k_select_single(const Params p) {
+__global__ __launch_bounds__(256) void k_select_zero(const Params p) {
+  uint32_t* hist = p.hist + (int64_t)blockIdx.x * kHistBins;
+  for (int i = threadIdx.x; i < kHistBins; i += 256) hist[i] = 0u;
+}
+
+// 4096 tokens per workgroup: histogram in LDS first, then one global atomic per bin that
+// the workgroup touched (scores of one head crowd into a few dozen bins, so adding token
+// by token to global memory would serialise on those addresses).
+__global__ __launch_bounds__(kSelThreads) void k_select_hist(const Params p) {
+  const int bh = blockIdx.y, b = bh / p.Hkv;
+  const int N = seq_len(p, b);
+  const int tid = threadIdx.x;
+  const int j0 = blockIdx.x * (4 * kSelThreads);
+  if (j0 >= N) return;
+  __shared__ uint32_t lh[kHistBins];
+#pragma unroll
+  for (int u = 0; u < kHistBins / kSelThreads; ++u) lh[tid + u * kSelThreads] = 0u;
+  __syncthreads();
+  const float* sc = p.scores + (int64_t)bh * p.cap;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int j = j0 + u * kSelThreads + tid;
+    if (j < N) atomicAdd(&lh[float_key(sc[j]) >> kHistShift], 1u);
+  }
+  __syncthreads();
+  uint32_t* hist = p.hist + (int64_t)bh * kHistBins;
+#pragma unroll
+  for (int u = 0; u < kHistBins / kSelThreads; ++u) {
+    const uint32_t c = lh[tid + u * kSelThreads];
+    if (c) atomicAdd(&hist[tid + u * kSelThreads], c);
+  }
+}
+
+__global__ __launch_bounds__(kSelThreads) void k_select_main(const Params p) {
   const int bh = blockIdx.x, b = bh / p.Hkv;
   const int N = seq_len(p, b);
+  const int tid = threadIdx.x;
   const float* sc = p.scores + (int64_t)bh * p.cap;
   int32_t* out = p.kept + (int64_t)bh * p.budget;
   const int k = p.budget;
 
   if (N <= k) {                          // nothing to evict: identity, -1 padded
-    for (int i = threadIdx.x; i < k; i += kSelThreads) out[i] = i < N ? i : -1;
+    for (int i = tid; i < k; i += kSelThreads) out[i] = i < N ? i : -1;
     return;
   }
-  __shared__ int hist[256];
   __shared__ int wave_tot[kSelWaves];
+  __shared__ int hist[256];
   __shared__ uint32_t s_prefix;
-  __shared__ int s_krem;
+  __shared__ int s_krem, s_ncand;
+  extern __shared__ uint32_t cand[];     // [kCandMax]
 
-  uint32_t prefix = 0;                   // digits fixed so far (high bits)
-  int krem = k;                          // rank still to locate inside the prefix class
-  for (int pass = 0; pass < 4; ++pass) {
-    const int shift = 24 - 8 * pass;
-    const uint32_t himask = pass == 0 ? 0u : 0xffffffffu << (shift + 8);
-    if (threadIdx.x < 256) hist[threadIdx.x] = 0;
-    __syncthreads();
-    for (int j = threadIdx.x; j < N; j += kSelThreads) {
-      const uint32_t key = float_key(sc[j]);
-      if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+  // ---- 1. the histogram bin that holds the k-th largest key ----------------------------
+  {
+    const uint32_t* gh = p.hist + (int64_t)bh * kHistBins;
+    constexpr int BPT = kHistBins / kSelThreads;            // bins per thread
+    // thread t owns bins of descending value: reversed index so that a prefix scan over
+    // threads is a walk down from the largest key
+    const int top = kHistBins - 1 - tid * BPT;
+    int cnt[BPT], mine = 0;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) { cnt[i] = (int)gh[top - i]; mine += cnt[i]; }
+    int total;
+    int above = block_excl_scan(mine, wave_tot, total);
+    if (above < k && k <= above + mine) {                     // exactly one thread
+#pragma unroll
+      for (int i = 0; i < BPT; ++i) {
+        if (above < k && k <= above + cnt[i]) {
+          s_prefix = (uint32_t)(top - i) << kHistShift;
+          s_krem = k - above;
+          s_ncand = cnt[i];
+        }
+        above += cnt[i];
+      }
     }
     __syncthreads();
-    if (threadIdx.x == 0) {              // walk down from the largest digit
-      int rem = krem, dgt = 255;
-      for (; dgt > 0; --dgt) {
-        if (hist[dgt] >= rem) break;
-        rem -= hist[dgt];
+  }
+  uint32_t prefix = s_prefix;            // key bits fixed so far (high bits)
+  int krem = s_krem;                     // rank still to locate inside the prefix class
+  const int ncand = s_ncand;
+  const bool in_lds = ncand <= kCandMax;
+  __syncthreads();
+
+  // ---- 2. finish the radix search on the low 20 bits ------------------------------------
+  if (in_lds) {
+    if (tid == 0) s_ncand = 0;
+    __syncthreads();
+    const int lane = tid % kWave;
+    for (int j0 = 0; j0 < N; j0 += kSelThreads) {            // uniform trip count
+      const int j = j0 + tid;
+      const uint32_t key = j < N ? float_key(sc[j]) : 0u;
+      const bool hit = j < N && (key >> kHistShift) == (prefix >> kHistShift);
+      const uint64_t bal = __ballot(hit);                     // one LDS atomic per wave
+      int base = 0;
+      if (lane == 0 && bal) base = atomicAdd(&s_ncand, __popcll(bal));
+      base = __shfl(base, 0, kWave);
+      if (hit) cand[base + __popcll(bal & ((1ull << lane) - 1ull))] = key;
+    }
+    __syncthreads();
+  }
+  const int n_src = in_lds ? ncand : N;
+  int shift = kHistShift;
+  while (shift > 0) {
+    const int bits = shift >= 8 ? 8 : shift;
+    shift -= bits;
+    const uint32_t himask = 0xffffffffu << (shift + bits);
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int j = tid; j < n_src; j += kSelThreads) {
+      const uint32_t key = in_lds ? cand[j] : float_key(sc[j]);
+      if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & ((1u << bits) - 1u)], 1);
+    }
+    __syncthreads();
+    {                                    // walk down from the largest digit, in parallel:
+      const int nd = 1 << bits;          // thread t holds digit nd-1-t, a prefix scan counts
+      const int mine = tid < nd ? hist[nd - 1 - tid] : 0;     // the keys in larger digits
+      int total;
+      const int above = block_excl_scan(mine, wave_tot, total);
+      if (tid < nd && above < krem && krem <= above + mine) {  // exactly one thread
+        s_prefix = prefix | ((uint32_t)(nd - 1 - tid) << shift);
+        s_krem = krem - above;
       }
-      s_prefix = prefix | ((uint32_t)dgt << shift);
-      s_krem = rem;
     }
     __syncthreads();
     prefix = s_prefix;
@@ -76,26 +170,80 @@ __global__ __launch_bounds__(kSelThreads) void k_select_single(const Params p) {
   }
   // prefix = key of the k-th largest score; krem = how many of its ties are kept.
   const uint32_t theta = prefix;
-  int base_out = 0, ties_seen = 0;
-  for (int j0 = 0; j0 < N; j0 += kSelThreads) {
-    const int j = j0 + threadIdx.x;
-    const uint32_t key = j < N ? float_key(sc[j]) : 0u;
-    const bool gt = j < N && key > theta;
-    const bool eq = j < N && key == theta;
-    int eq_total, keep_total;
-    const int eq_before = block_excl_count(eq, wave_tot, eq_total);
-    const bool keep = gt || (eq && ties_seen + eq_before < krem);
-    const int pos = block_excl_count(keep, wave_tot, keep_total);
-    if (keep) out[base_out + pos] = j;
-    base_out += keep_total;
-    ties_seen += eq_total;
+
+  // ---- 3. emit, ascending: each wave owns a contiguous span, read 64 tokens at a time ------
+  const int lane = tid % kWave, wv = tid / kWave;
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const int span = ((N + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
+  const int s0 = min(N, wv * span), s1 = min(N, s0 + span);
+  const int iters = span / kWave;
+  constexpr int kIterReg = 32;           // spans up to 32 x 64 tokens stay in registers
+  const bool in_regs = iters <= kIterReg;
+  uint32_t keys[kIterReg];
+  int w_gt = 0, w_eq = 0;                // wave-uniform counts
+  if (in_regs) {
+#pragma unroll
+    for (int it = 0; it < kIterReg; ++it) {
+      const int j = s0 + it * kWave + lane;
+      keys[it] = j < s1 ? float_key(sc[j]) : 0u;
+    }
+#pragma unroll
+    for (int it = 0; it < kIterReg; ++it) {
+      const bool valid = s0 + it * kWave + lane < s1;
+      w_gt += __popcll(__ballot(valid && keys[it] > theta));
+      w_eq += __popcll(__ballot(valid && keys[it] == theta));
+    }
+  } else {
+    for (int it = 0; it < iters; ++it) {
+      const int j = s0 + it * kWave + lane;
+      const uint32_t key = j < s1 ? float_key(sc[j]) : 0u;
+      w_gt += __popcll(__ballot(j < s1 && key > theta));
+      w_eq += __popcll(__ballot(j < s1 && key == theta));
+    }
+  }
+  __shared__ int wave_eq[kSelWaves], wave_keep[kSelWaves];
+  if (lane == 0) wave_eq[wv] = w_eq;
+  __syncthreads();
+  int eq_before = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) eq_before += w < wv ? wave_eq[w] : 0;
+  int ties_left = max(0, min(w_eq, krem - eq_before));        // ties this wave may keep
+  if (lane == 0) wave_keep[wv] = w_gt + ties_left;
+  __syncthreads();
+  int pos = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) pos += w < wv ? wave_keep[w] : 0;
+  auto emit = [&](int it, uint32_t key) {
+    const int j = s0 + it * kWave + lane;
+    const bool valid = j < s1;
+    const bool gt = valid && key > theta, eq = valid && key == theta;
+    const uint64_t eqm = __ballot(eq);
+    const bool keep = gt || (eq && __popcll(eqm & lt_mask) < ties_left);
+    const uint64_t km = __ballot(keep);
+    if (keep) out[pos + __popcll(km & lt_mask)] = j;
+    pos += __popcll(km);
+    ties_left -= min(ties_left, (int)__popcll(eqm));
+  };
+  if (in_regs) {
+#pragma unroll
+    for (int it = 0; it < kIterReg; ++it) emit(it, keys[it]);
+  } else {
+    for (int it = 0; it < iters; ++it) {
+      const int j = s0 + it * kWave + lane;
+      emit(it, j < s1 ? float_key(sc[j]) : 0u);
+    }
   }
 }
 
 }  // namespace
 
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook) {
-  hipLaunchKernelGGL(k_select_single, dim3(p.B * p.Hkv), dim3(kSelThreads), 0, s, p);
+  if (!p.hist_zeroed) hipLaunchKernelGGL(k_select_zero, dim3(p.B * p.Hkv), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(k_select_hist, dim3((p.cap + 4 * kSelThreads - 1) / (4 * kSelThreads), p.B * p.Hkv),
+                     dim3(kSelThreads), 0, s, p);
+  mark(hook, "select_hist");
+  hipLaunchKernelGGL(k_select_main, dim3(p.B * p.Hkv), dim3(kSelThreads),
+                     kCandMax * sizeof(uint32_t), s, p);
   mark(hook, "select");
   return hipGetLastError();
 }
