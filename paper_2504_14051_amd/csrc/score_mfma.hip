@@ -29,6 +29,21 @@ constexpr int kTN = 64;                 // keys per LDS tile
 constexpr int kD = 128;
 constexpr int kRowBytes = kD * 2;       // 256
 constexpr int kChunks = kRowBytes / 16; // 16-byte chunks per key row
+constexpr int kNBuf = 3;                // LDS ring of key tiles: loads run kNBuf-1 tiles ahead
+
+// global_load_lds_dwordx4: lane L of the wave copies 16 bytes from its own global address
+// to LDS byte address lds_base + 16 L (lds_base is wave-uniform and travels in M0).  Issued
+// through inline assembly so that the compiler does not serialise it against the LDS reads
+// of other ring slots; the matching waits are wait_vmcnt<N>() below.
+__device__ __forceinline__ void load_to_lds16(const void* gaddr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               : : "v"(gaddr), "s"(lds_base) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
 
 __device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes + ((chunk ^ (row & 15)) << 4); }
 
@@ -51,7 +66,7 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
   const int wr = wave / WK, kw = wave % WK;
   const int P = p.wic ? N - p.W : N;    // keys below P are visible to every row
 
-  __shared__ __attribute__((aligned(16))) unsigned char Ks[2][kTN * kRowBytes];
+  __shared__ __attribute__((aligned(16))) unsigned char Ks[kNBuf][kTN * kRowBytes];
   __shared__ float a_lds[2][WR][kTN];
   __shared__ int iw_lds[ROWS];          // window position of each row of the group
   __shared__ float st_lds[WK][ROWS][2];
@@ -94,28 +109,23 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
       }
     }
     // ---- sweep over the key tiles of this split --------------------------------------
-    // Global loads run two tiles ahead of the math (two register sets), LDS is double
-    // buffered: tile t+2 is fetched while tile t is computed and lands in the LDS buffer
-    // that tile t used, one barrier later.
-    struct Fetch { uint4 u0, u1, u2, u3; };                 // one thread's share of a tile
-    auto gload = [&](int t) -> Fetch {
-      auto one = [&](int u) -> uint4 {
-        const int id = tid + u * kThreads, row = id / kChunks, ch = id % kChunks;
-        const int j = min(c0 + t * kTN + row, N - 1);      // rows past the end repeat the last one
-        return *reinterpret_cast<const uint4*>(Kb + j * krow + ch * 16);
-      };
-      return Fetch{one(0), one(1), one(2), one(3)};
-    };
-    auto lstore = [&](int buf, const Fetch f) {
-      auto one = [&](int u, const uint4 v) {
-        const int id = tid + u * kThreads, row = id / kChunks, ch = id % kChunks;
-        *reinterpret_cast<uint4*>(&Ks[buf][swz(row, ch)]) = v;
-      };
-      one(0, f.u0); one(1, f.u1); one(2, f.u2); one(3, f.u3);
+    // K tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane L of
+    // a wave fills the 16-byte slot base + 16 L), kNBuf-1 tiles ahead of the math.  The
+    // XOR swizzle that keeps the fragment reads conflict-free is applied on the global
+    // side: the lane that owns slot (row, pc) fetches chunk pc ^ (row & 15) of that row.
+    auto issue = [&](int t, int buf) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int slot = (wave * 4 + u) * kWave + lane;      // 16-byte slot inside the tile
+        const int row = slot / kChunks, pc = slot % kChunks;
+        const int j = min(c0 + t * kTN + row, N - 1);        // rows past the end repeat the last one
+        load_to_lds16(Kb + j * krow + ((pc ^ (row & 15)) << 4),
+                      __builtin_amdgcn_readfirstlane(lds_addr(&Ks[buf][(wave * 4 + u) * kWave * 16])));
+      }
     };
     // One 64-key tile out of LDS buffer `buf`.  TAIL: some logits of the tile are masked
     // (keys past the end of the cache, or window keys a row must not see).
-    auto tile = [&](auto tail_tag, int buf, int tile0) {
+    auto tile = [&](auto tail_tag, int buf, int abuf, int tile0) {
       constexpr bool TAIL = decltype(tail_tag)::value;
 #pragma unroll
       for (int kbi = 0; kbi < KBW; ++kbi) {
@@ -173,14 +183,14 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
             }
           }
           cs += __shfl_xor(cs, 32, kWave);
-          if (lane < 32) a_lds[buf][wr][kb * 32 + lane] = cs;
+          if (lane < 32) a_lds[abuf][wr][kb * 32 + lane] = cs;
         }
       }
     };
-    auto math = [&](int t, int buf) {
+    auto math = [&](int t, int buf, int abuf) {
       const int tile0 = c0 + t * kTN;
-      if (tile0 + kTN > min(P, N)) tile(std::true_type{}, buf, tile0);
-      else                         tile(std::false_type{}, buf, tile0);
+      if (tile0 + kTN > min(P, N)) tile(std::true_type{}, buf, abuf, tile0);
+      else                         tile(std::false_type{}, buf, abuf, tile0);
     };
     auto flush_a = [&](int t, int buf) {                     // after the barrier of step t
       const int tile0 = c0 + t * kTN;
@@ -192,28 +202,32 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
         else a_out[tile0 + tid] += s;                          // later row groups add on
       }
     };
-    // Loop step t: fetch tile t+2 into the register set that tile t came from, do the math
-    // of tile t, move tile t+1 from its registers into the other LDS buffer.  The two
-    // register sets are separate named values, so the loads stay in flight across the math.
-    __syncthreads();                     // previous row group is done with LDS
-    Fetch fa = gload(0), fb = fa;
-    if (ntiles > 1) fb = gload(1);
-    lstore(0, fa);
-    __syncthreads();
-    for (int t = 0; t < ntiles; t += 2) {
-      if (t + 2 < ntiles) fa = gload(t + 2);
-      math(t, 0);
-      if (t + 1 < ntiles) lstore(1, fb);
-      __syncthreads();
-      flush_a(t, 0);
-      if (t + 1 < ntiles) {
-        if (t + 3 < ntiles) fb = gload(t + 3);
-        math(t + 1, 1);
-        if (t + 2 < ntiles) lstore(0, fa);
-        __syncthreads();
-        flush_a(t + 1, 1);
+    // Make the compiler finish its own global loads (Q fragments, normalisers) here: a wait
+    // it placed inside the tile loop would also drain the LDS loads that must stay in flight.
+#pragma unroll
+    for (int rb = 0; rb < RBW; ++rb) {
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qf[rb][ks]));
+      if (MODE == 1) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) asm volatile("" : : "v"(lse[rb][i]));
       }
     }
+    __syncthreads();                     // previous row group is done with LDS
+    for (int t = 0; t < kNBuf - 1 && t < ntiles; ++t) issue(t, t);
+    int buf = 0;
+    for (int t = 0; t < ntiles; ++t) {
+      // this wave's share of tile t has landed once at most the 4 loads of tile t+1 are
+      // still in flight (loads complete in order; a store in between cannot hide a load)
+      if (t + 1 < ntiles) wait_vmcnt<4>(); else wait_vmcnt<0>();
+      __syncthreads();                   // ... and so has everyone else's; tile t-1 is done with
+      if (t > 0) flush_a(t - 1, (t - 1) & 1);
+      if (t + kNBuf - 1 < ntiles) issue(t + kNBuf - 1, buf == 0 ? kNBuf - 1 : buf - 1);
+      math(t, buf, t & 1);
+      buf = buf + 1 == kNBuf ? 0 : buf + 1;
+    }
+    __syncthreads();
+    flush_a(ntiles - 1, (ntiles - 1) & 1);
     // ---- end of sweep 1: merge the two half-waves, then the key waves ------------------
     if (MODE == 0) {
 #pragma unroll

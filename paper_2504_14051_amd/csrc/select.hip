@@ -3,12 +3,14 @@
 // Scores are compared through their order-preserving 32-bit integer image, so the whole
 // selection is integer work: exact, and independent of launch shape.
 //   1. a 4096-bin histogram of the top 12 key bits per head (k_select_hist);
-//   2. one workgroup per head walks the histogram from the top to the bin that holds the
-//      budget-th largest score, gathers that bin's keys into LDS and finishes the radix
-//      search on the remaining 20 bits there (three short passes);
+//   2. one workgroup per head (k_select_main) walks the histogram from the top to the bin
+//      that holds the budget-th largest score, gathers that bin's keys into LDS and
+//      finishes the radix search on the remaining 20 bits there (three short passes);
 //   3. the same workgroup emits the kept indices in ascending order: every wave owns a
 //      contiguous span of the tokens and places its survivors by ballot and popcount.
 // Equal scores at the threshold keep the lower indices.
+// Each wave reads its span once, 64 tokens per load, and keeps the keys in registers
+// (up to 32 loads in flight per lane) for both the gather and the emit.
 #include "common.hpp"
 
 namespace caote {
@@ -17,6 +19,7 @@ namespace {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kCandMax = 12288;          // keys of the threshold bin held in LDS
+constexpr int kIterReg = 32;             // spans up to 32 x 64 tokens per wave stay in registers
 
 // Exclusive prefix sum of v over the block (threads in order) and the block total.
 __device__ __forceinline__ int block_excl_scan(int v, int* wave_tot, int& total) {
@@ -60,11 +63,15 @@ __global__ __launch_bounds__(kSelThreads) void k_select_hist(const Params p) {
   for (int u = 0; u < kHistBins / kSelThreads; ++u) lh[tid + u * kSelThreads] = 0u;
   __syncthreads();
   const float* sc = p.scores + (int64_t)bh * p.cap;
+  uint32_t key[4];
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const int j = j0 + u * kSelThreads + tid;
-    if (j < N) atomicAdd(&lh[float_key(sc[j]) >> kHistShift], 1u);
+    key[u] = j < N ? float_key(sc[j]) : 0u;
   }
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (j0 + u * kSelThreads + tid < N) atomicAdd(&lh[key[u] >> kHistShift], 1u);
   __syncthreads();
   uint32_t* hist = p.hist + (int64_t)bh * kHistBins;
 #pragma unroll
@@ -74,10 +81,12 @@ __global__ __launch_bounds__(kSelThreads) void k_select_hist(const Params p) {
   }
 }
 
+// IN_REGS: every wave's span fits kIterReg loads per lane (N <= 32768).
+template <bool IN_REGS>
 __global__ __launch_bounds__(kSelThreads) void k_select_main(const Params p) {
   const int bh = blockIdx.x, b = bh / p.Hkv;
   const int N = seq_len(p, b);
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
   const float* sc = p.scores + (int64_t)bh * p.cap;
   int32_t* out = p.kept + (int64_t)bh * p.budget;
   const int k = p.budget;
@@ -86,11 +95,44 @@ __global__ __launch_bounds__(kSelThreads) void k_select_main(const Params p) {
     for (int i = tid; i < k; i += kSelThreads) out[i] = i < N ? i : -1;
     return;
   }
-  __shared__ int wave_tot[kSelWaves];
+  __shared__ int wave_tot[kSelWaves], wave_eq[kSelWaves], wave_keep[kSelWaves];
   __shared__ int hist[256];
   __shared__ uint32_t s_prefix;
   __shared__ int s_krem, s_ncand;
   extern __shared__ uint32_t cand[];     // [kCandMax]
+
+  // Span of this wave: [s0, s1), read as `iters` rows of 64 consecutive tokens.
+  const uint64_t lt_mask = (1ull << lane) - 1ull;
+  const int span = ((N + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
+  const int s0 = min(N, wv * span), s1 = min(N, s0 + span);
+  const int iters = span / kWave;
+  uint32_t keys[IN_REGS ? kIterReg : 1];
+  if (IN_REGS) {                         // all loads of the span in flight at once
+#pragma unroll
+    for (int it = 0; it < kIterReg; ++it) {
+      const int j = s0 + it * kWave + lane;
+      keys[it] = j < s1 ? float_key(sc[j]) : 0u;
+    }
+  }
+  // Applies f(it, key, valid) to every row of the span, in order.
+  auto for_span = [&](auto&& f) {
+    if (IN_REGS) {
+#pragma unroll
+      for (int it = 0; it < kIterReg; ++it) f(it, keys[it], s0 + it * kWave + lane < s1);
+    } else {
+      for (int it0 = 0; it0 < iters; it0 += 8) {               // 8 loads in flight
+        uint32_t kk[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int j = s0 + (it0 + u) * kWave + lane;
+          kk[u] = j < s1 ? float_key(sc[j]) : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (it0 + u < iters) f(it0 + u, kk[u], s0 + (it0 + u) * kWave + lane < s1);
+      }
+    }
+  };
 
   // ---- 1. the histogram bin that holds the k-th largest key ----------------------------
   {
@@ -124,20 +166,23 @@ __global__ __launch_bounds__(kSelThreads) void k_select_main(const Params p) {
   __syncthreads();
 
   // ---- 2. finish the radix search on the low 20 bits ------------------------------------
-  if (in_lds) {
+  if (in_lds) {                          // gather the threshold bin's keys (order is irrelevant)
     if (tid == 0) s_ncand = 0;
     __syncthreads();
-    const int lane = tid % kWave;
-    for (int j0 = 0; j0 < N; j0 += kSelThreads) {            // uniform trip count
-      const int j = j0 + tid;
-      const uint32_t key = j < N ? float_key(sc[j]) : 0u;
-      const bool hit = j < N && (key >> kHistShift) == (prefix >> kHistShift);
-      const uint64_t bal = __ballot(hit);                     // one LDS atomic per wave
-      int base = 0;
-      if (lane == 0 && bal) base = atomicAdd(&s_ncand, __popcll(bal));
-      base = __shfl(base, 0, kWave);
-      if (hit) cand[base + __popcll(bal & ((1ull << lane) - 1ull))] = key;
-    }
+    const uint32_t bin = prefix >> kHistShift;
+    int w_hits = 0;
+    for_span([&](int, uint32_t key, bool valid) {
+      w_hits += __popcll(__ballot(valid && (key >> kHistShift) == bin));
+    });
+    int base = 0;
+    if (lane == 0 && w_hits) base = atomicAdd(&s_ncand, w_hits);   // one LDS atomic per wave
+    base = __shfl(base, 0, kWave);
+    for_span([&](int, uint32_t key, bool valid) {
+      const bool hit = valid && (key >> kHistShift) == bin;
+      const uint64_t bal = __ballot(hit);
+      if (hit) cand[base + __popcll(bal & lt_mask)] = key;
+      base += __popcll(bal);
+    });
     __syncthreads();
   }
   const int n_src = in_lds ? ncand : N;
@@ -171,37 +216,12 @@ __global__ __launch_bounds__(kSelThreads) void k_select_main(const Params p) {
   // prefix = key of the k-th largest score; krem = how many of its ties are kept.
   const uint32_t theta = prefix;
 
-  // ---- 3. emit, ascending: each wave owns a contiguous span, read 64 tokens at a time ------
-  const int lane = tid % kWave, wv = tid / kWave;
-  const uint64_t lt_mask = (1ull << lane) - 1ull;
-  const int span = ((N + kSelWaves - 1) / kSelWaves + kWave - 1) / kWave * kWave;
-  const int s0 = min(N, wv * span), s1 = min(N, s0 + span);
-  const int iters = span / kWave;
-  constexpr int kIterReg = 32;           // spans up to 32 x 64 tokens stay in registers
-  const bool in_regs = iters <= kIterReg;
-  uint32_t keys[kIterReg];
+  // ---- 3. emit, ascending -----------------------------------------------------------------
   int w_gt = 0, w_eq = 0;                // wave-uniform counts
-  if (in_regs) {
-#pragma unroll
-    for (int it = 0; it < kIterReg; ++it) {
-      const int j = s0 + it * kWave + lane;
-      keys[it] = j < s1 ? float_key(sc[j]) : 0u;
-    }
-#pragma unroll
-    for (int it = 0; it < kIterReg; ++it) {
-      const bool valid = s0 + it * kWave + lane < s1;
-      w_gt += __popcll(__ballot(valid && keys[it] > theta));
-      w_eq += __popcll(__ballot(valid && keys[it] == theta));
-    }
-  } else {
-    for (int it = 0; it < iters; ++it) {
-      const int j = s0 + it * kWave + lane;
-      const uint32_t key = j < s1 ? float_key(sc[j]) : 0u;
-      w_gt += __popcll(__ballot(j < s1 && key > theta));
-      w_eq += __popcll(__ballot(j < s1 && key == theta));
-    }
-  }
-  __shared__ int wave_eq[kSelWaves], wave_keep[kSelWaves];
+  for_span([&](int, uint32_t key, bool valid) {
+    w_gt += __popcll(__ballot(valid && key > theta));
+    w_eq += __popcll(__ballot(valid && key == theta));
+  });
   if (lane == 0) wave_eq[wv] = w_eq;
   __syncthreads();
   int eq_before = 0;
@@ -213,37 +233,30 @@ __global__ __launch_bounds__(kSelThreads) void k_select_main(const Params p) {
   int pos = 0;
 #pragma unroll
   for (int w = 0; w < kSelWaves; ++w) pos += w < wv ? wave_keep[w] : 0;
-  auto emit = [&](int it, uint32_t key) {
-    const int j = s0 + it * kWave + lane;
-    const bool valid = j < s1;
+  for_span([&](int it, uint32_t key, bool valid) {
     const bool gt = valid && key > theta, eq = valid && key == theta;
     const uint64_t eqm = __ballot(eq);
-    const bool keep = gt || (eq && __popcll(eqm & lt_mask) < ties_left);
+    const bool keep = gt || (eq && (int)__popcll(eqm & lt_mask) < ties_left);
     const uint64_t km = __ballot(keep);
-    if (keep) out[pos + __popcll(km & lt_mask)] = j;
+    if (keep) out[pos + __popcll(km & lt_mask)] = s0 + it * kWave + lane;
     pos += __popcll(km);
     ties_left -= min(ties_left, (int)__popcll(eqm));
-  };
-  if (in_regs) {
-#pragma unroll
-    for (int it = 0; it < kIterReg; ++it) emit(it, keys[it]);
-  } else {
-    for (int it = 0; it < iters; ++it) {
-      const int j = s0 + it * kWave + lane;
-      emit(it, j < s1 ? float_key(sc[j]) : 0u);
-    }
-  }
+  });
 }
 
 }  // namespace
 
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook) {
-  if (!p.hist_zeroed) hipLaunchKernelGGL(k_select_zero, dim3(p.B * p.Hkv), dim3(256), 0, s, p);
-  hipLaunchKernelGGL(k_select_hist, dim3((p.cap + 4 * kSelThreads - 1) / (4 * kSelThreads), p.B * p.Hkv),
+  const int bh = p.B * p.Hkv;
+  if (!p.hist_zeroed) hipLaunchKernelGGL(k_select_zero, dim3(bh), dim3(256), 0, s, p);
+  hipLaunchKernelGGL(k_select_hist, dim3((p.cap + 4 * kSelThreads - 1) / (4 * kSelThreads), bh),
                      dim3(kSelThreads), 0, s, p);
   mark(hook, "select_hist");
-  hipLaunchKernelGGL(k_select_main, dim3(p.B * p.Hkv), dim3(kSelThreads),
-                     kCandMax * sizeof(uint32_t), s, p);
+  const size_t lds = kCandMax * sizeof(uint32_t);
+  if (p.cap <= kIterReg * kWave * kSelWaves)
+    hipLaunchKernelGGL(k_select_main<true>, dim3(bh), dim3(kSelThreads), lds, s, p);
+  else
+    hipLaunchKernelGGL(k_select_main<false>, dim3(bh), dim3(kSelThreads), lds, s, p);
   mark(hook, "select");
   return hipGetLastError();
 }
