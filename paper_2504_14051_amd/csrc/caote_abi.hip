@@ -58,6 +58,9 @@ caote_status check_layout(const caote_layout* L, int32_t budget, bool need_budge
   if ((int64_t)L->batch * L->n_kv_heads > 65535)
     return fail(CAOTE_EUNSUPPORTED, "batch * n_kv_heads > 65535");
   if (need_budget && budget < 1) return fail(CAOTE_EINVAL, "budget must be >= 1");
+  if (need_budget && L->capacity > caote::kSelSpan * caote::kMaxSpans)
+    return fail(CAOTE_EUNSUPPORTED, "selection supports at most %d tokens per head",
+                caote::kSelSpan * caote::kMaxSpans);
   return CAOTE_OK;
 }
 
@@ -100,6 +103,10 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.zpart = (float*)carve((size_t)BH * p.n_vchunk * sizeof(float));
   p.osum = (float*)carve((size_t)BH * (caote::kMaxD + 1) * sizeof(float));
   p.hist = (uint32_t*)carve((size_t)BH * caote::kHistBins * sizeof(uint32_t));
+  p.n_span = ceil_div(p.cap, caote::kSelSpan);
+  p.sel_cand = (uint32_t*)carve((size_t)BH * p.cap * sizeof(uint32_t));
+  p.sel_rec = (int32_t*)carve((size_t)BH * p.n_span * 2 * sizeof(int32_t));
+  p.sel_head = (int32_t*)carve((size_t)BH * 4 * sizeof(int32_t));
   const size_t row_bytes = (size_t)p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
   const int bud = budget > 0 ? budget : 0;
   p.stage = carve((size_t)BH * bud * (2 * row_bytes + sizeof(float)));

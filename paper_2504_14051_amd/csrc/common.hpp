@@ -13,6 +13,8 @@ constexpr int kVChunk = 256;      // tokens per workgroup in the value sweeps
 constexpr int kMaxD = 128;        // largest head_dim
 constexpr int kHistBins = 4096;   // selection histogram: top 12 bits of the score key
 constexpr int kHistShift = 20;
+constexpr int kSelSpan = 2048;    // tokens per workgroup in the selection kernels
+constexpr int kMaxSpans = 1024;   // spans per head the selection supports (2M tokens)
 
 // Everything a kernel needs to know about one call.  Passed by value.
 struct Params {
@@ -37,6 +39,10 @@ struct Params {
   float* zpart;       // [BH][n_vchunk]        partial sum of h_j
   float* osum;        // [BH][kMaxD+1]         sum h_j v_j (un-normalised) and, last, Z
   uint32_t* hist;     // [BH][kHistBins]       histogram of the score keys
+  uint32_t* sel_cand; // [BH][cap]             keys of the threshold bin, one list per span
+  int32_t* sel_rec;   // [BH][n_span][2]       per span: keys in higher bins, list length
+  int32_t* sel_head;  // [BH][4]               threshold bin, rank inside it, its population
+  int n_span;
   int hist_zeroed;    // an earlier kernel of this call has cleared `hist` (fused call)
   void* stage;        // compaction staging
   int n_split, split_len, Rp, n_vchunk, vchunk_len;
