@@ -66,6 +66,32 @@ def phase_bytes(wl, name):
     return table.get(name)
 
 
+# Kernel(s) behind each phase name that caote_evict_timed reports.
+PHASE_KERNELS = {
+    "key_rowstats": r"k_logits_\w+<.*, 0>$", "key_colsum": r"k_logits_\w+<.*, 1>$",
+    "merge_stats": r"k_merge_stats", "value_sum": r"k_vsum", "value_final": r"k_vfinal",
+    "value_score": r"k_vscore", "select_hist": r"k_select_hist", "select_span": r"k_select_span",
+    "select_emit": r"k_select_emit", "compact_gather": r"k_move_rows<0>", "compact_scatter": r"k_move_rows<1>",
+}
+
+
+def measured_traffic(workload, phase):
+    """HBM-side bytes per launch of the phase's kernel from the committed counter summary
+    (profiles/traffic_<workload>.json, written from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    runs of this script), or None if there is none."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.json")
+    pat = PHASE_KERNELS.get(phase)
+    if not pat or not os.path.exists(path):
+        return None
+    with open(path) as f:
+        kernels = json.load(f)["kernels"]
+    hits = [v for k, v in kernels.items() if re.search(pat, k)]
+    if not hits:
+        return None
+    return sum(v["fetch_bytes"] + v["write_bytes"] for v in hits)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +140,14 @@ def main():
     scores = torch.empty(wl.batch, wl.n_kv_heads, wl.context, device="cuda")
     kept = torch.empty(wl.batch, wl.n_kv_heads, wl.budget, dtype=torch.int32, device="cuda")
     stream = torch.cuda.current_stream()
+
+    # A plain copy of known size (256 MiB read + 256 MiB written), so that a counter run
+    # of this script (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE) can be scaled to bytes.
+    calib_src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
 
     def step(i):
         q, K, V, base = layers[i % n_layers]
@@ -184,7 +218,8 @@ def main():
                    "entry_point": "caote_evict",
                    "launch": "stream" if args.no_graph else "hip_graph"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(wl.name, dom),
                      "bytes_per_launch": dom_bytes, "ms_per_launch": phases[dom]},
         "path": {"algorithmic_bytes": alg["total"], "achieved": path_gbs, "peak": HBM_PEAK_GBS,
                  "unit": "GB/s", "frac": path_gbs / HBM_PEAK_GBS},

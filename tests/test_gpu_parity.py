@@ -269,3 +269,45 @@ def test_compact_hazard_patterns(B, oracle, pattern, dtype, d):
     torch.cuda.synchronize()
     cache = synth.Cache(None, None, K, V, base, None)
     H.check_compaction(oracle, K, V, base, dK.cpu(), dV.cpu(), db.cpu(), kept.numpy(), cache, budget)
+
+
+def test_hip_graph_replays_match_eager(B):
+    """The calls neither allocate nor synchronise, so they can be captured; every replay,
+    with eager work and synchronisation in between, must give the eager bits."""
+    wl = synth.llama3_8b_4k()
+    cache = synth.make_cache(wl, base_init="random")
+    dev = H.to_device(cache)
+    L = B.layout_for(wl, dev)
+    ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
+    shape = dev.K.shape[:3]
+    base0 = dev.base.clone()
+
+    def run(scores, kept, base, stream=None):
+        B.caote_score(dev.q, dev.K, dev.V, base, L, scores, ws, stream)
+        B.caote_select(scores, L, wl.budget, kept, ws, stream)
+
+    e_scores, e_kept, e_base = torch.empty(shape, device="cuda"), \
+        torch.empty((*shape[:2], wl.budget), dtype=torch.int32, device="cuda"), base0.clone()
+    run(e_scores, e_kept, e_base)
+    torch.cuda.synchronize()
+
+    g_scores, g_kept, g_base = torch.zeros_like(e_scores), torch.zeros_like(e_kept), base0.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        run(g_scores, g_kept, g_base, side)          # warm up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run(g_scores, g_kept, g_base, side)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        g_base.copy_(base0)                          # eager work between the replays
+        g_scores.zero_()
+        g_kept.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(g_scores, e_scores), f"replay {rep}: scores differ from the eager call"
+        assert torch.equal(g_kept, e_kept), f"replay {rep}: kept indices differ"
+        assert torch.equal(g_base, e_base), f"replay {rep}: accumulator differs"
