@@ -69,6 +69,7 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
   __shared__ __attribute__((aligned(16))) unsigned char Ks[kNBuf][kTN * kRowBytes];
   __shared__ float a_lds[2][WR][kTN];
   __shared__ int iw_lds[ROWS];          // window position of each row of the group
+  __shared__ float lse_lds[ROWS];       // sweep 2: normaliser of each row of the group
   __shared__ float st_lds[WK][ROWS][2];
 
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.K) +
@@ -77,8 +78,30 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
   float* a_out = p.a + (int64_t)bh * p.cap;
 
   for (int rg0 = 0; rg0 < p.R; rg0 += ROWS) {
+    // ---- sweep over the key tiles of this split --------------------------------------
+    // K tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane L of
+    // a wave fills the 16-byte slot base + 16 L), kNBuf-1 tiles ahead of the math.  The
+    // XOR swizzle that keeps the fragment reads conflict-free is applied on the global
+    // side: the lane that owns slot (row, pc) fetches chunk pc ^ (row & 15) of that row.
+    auto issue = [&](int t, int buf) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int slot = (wave * 4 + u) * kWave + lane;      // 16-byte slot inside the tile
+        const int row = slot / kChunks, pc = slot % kChunks;
+        const int j = min(c0 + t * kTN + row, N - 1);        // rows past the end repeat the last one
+        load_to_lds16(Kb + j * krow + ((pc ^ (row & 15)) << 4),
+                      __builtin_amdgcn_readfirstlane(lds_addr(&Ks[buf][(wave * 4 + u) * kWave * 16])));
+      }
+    };
+    // The first two K tiles are requested before anything else, so that their latency
+    // overlaps the set-up below.
+    __syncthreads();                     // previous row group is done with LDS
+    for (int t = 0; t < kNBuf - 1 && t < ntiles; ++t) issue(t, t);
     // ---- per-row-group set-up: Q fragments, window positions, normalisers ----------
-    for (int i = tid; i < ROWS; i += kThreads) iw_lds[i] = (rg0 + i) < p.R ? (rg0 + i) % p.W : -1;
+    for (int i = tid; i < ROWS; i += kThreads) {
+      iw_lds[i] = (rg0 + i) < p.R ? (rg0 + i) % p.W : -1;
+      if (MODE == 1) lse_lds[i] = (rg0 + i) < p.R ? p.lse2[(int64_t)bh * p.Rp + rg0 + i] : INFINITY;
+    }
     bf16x8 qf[RBW][8];
     float lse[RBW][16];
     float m_run[RBW], l_run[RBW];
@@ -100,29 +123,14 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
       }
-      if (MODE == 1) {
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int rr = rbase + m_of(i, lane);
-          lse[rb][i] = rr < p.R ? p.lse2[(int64_t)bh * p.Rp + rr] : INFINITY;
-        }
-      }
     }
-    // ---- sweep over the key tiles of this split --------------------------------------
-    // K tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane L of
-    // a wave fills the 16-byte slot base + 16 L), kNBuf-1 tiles ahead of the math.  The
-    // XOR swizzle that keeps the fragment reads conflict-free is applied on the global
-    // side: the lane that owns slot (row, pc) fetches chunk pc ^ (row & 15) of that row.
-    auto issue = [&](int t, int buf) {
+    if (MODE == 1) {
+      __syncthreads();
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int slot = (wave * 4 + u) * kWave + lane;      // 16-byte slot inside the tile
-        const int row = slot / kChunks, pc = slot % kChunks;
-        const int j = min(c0 + t * kTN + row, N - 1);        // rows past the end repeat the last one
-        load_to_lds16(Kb + j * krow + ((pc ^ (row & 15)) << 4),
-                      __builtin_amdgcn_readfirstlane(lds_addr(&Ks[buf][(wave * 4 + u) * kWave * 16])));
-      }
-    };
+      for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) lse[rb][i] = lse_lds[(wr * RBW + rb) * 32 + m_of(i, lane)];
+    }
     // One 64-key tile out of LDS buffer `buf`.  TAIL: some logits of the tile are masked
     // (keys past the end of the cache, or window keys a row must not see).
     auto tile = [&](auto tail_tag, int buf, int abuf, int tile0) {
@@ -213,8 +221,6 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
         for (int i = 0; i < 16; ++i) asm volatile("" : : "v"(lse[rb][i]));
       }
     }
-    __syncthreads();                     // previous row group is done with LDS
-    for (int t = 0; t < kNBuf - 1 && t < ntiles; ++t) issue(t, t);
     int buf = 0;
     for (int t = 0; t < ntiles; ++t) {
       // this wave's share of tile t has landed once at most the 4 loads of tile t+1 are
