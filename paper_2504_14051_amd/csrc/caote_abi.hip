@@ -34,6 +34,8 @@ caote_status check_layout(const caote_layout* L, int32_t budget, bool need_budge
   if (L->head_dim != 64 && L->head_dim != 128)
     return fail(CAOTE_EUNSUPPORTED, "head_dim %d: only 64 and 128 are supported", L->head_dim);
   if (L->window < 1) return fail(CAOTE_EINVAL, "window must be >= 1");
+  if ((int64_t)L->window * (L->n_q_heads / L->n_kv_heads) > (1 << 20))
+    return fail(CAOTE_EUNSUPPORTED, "more than 2^20 query rows per KV head");
   if (L->capacity < 1) return fail(CAOTE_EINVAL, "capacity must be >= 1");
   if (L->dtype != CAOTE_BF16 && L->dtype != CAOTE_F32) return fail(CAOTE_EINVAL, "unknown dtype %d", L->dtype);
   if (L->base < CAOTE_BASE_NONE || L->base > CAOTE_BASE_SNAPKV) return fail(CAOTE_EINVAL, "unknown base %d", L->base);
@@ -77,6 +79,7 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.ph = L->n_protect_head; p.pt = L->n_protect_tail; p.variant = L->variant; p.dtype = L->dtype;
   p.budget = budget;
   p.c2 = L->softmax_scale * 1.4426950408889634f;
+  p.rcpW = 1.0f / (float)L->window;
 
   const int BH = p.B * p.Hkv;
   // Token chunk per workgroup: about `target` workgroups per launch, whole 64-key tiles.

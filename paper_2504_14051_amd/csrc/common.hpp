@@ -30,6 +30,7 @@ struct Params {
   int base_mode, pool, wic, ph, pt, variant, dtype;
   int budget, mode;
   float c2;           // softmax_scale * log2(e): logits are handled in the log2 domain
+  float rcpW;         // 1 / W, for row -> (query head, window position) without integer division
   // ---- workspace ----
   float* stats;       // [BH][n_split][Rp][2]  partial (max, sum) per query row
   float* lse2;        // [BH][Rp]              log2-sum-exp2 per query row
@@ -80,6 +81,14 @@ __device__ __forceinline__ float team_sum(float v) {
 #pragma unroll
   for (int m = TL / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
   return v;
+}
+
+// r = q * W + m with 0 <= m < W, for 0 <= r < 2^22: float estimate, one correction step.
+__device__ __forceinline__ void divmod_w(const Params& p, int r, int& q, int& m) {
+  q = (int)((float)r * p.rcpW);
+  m = r - q * p.W;
+  if (m < 0) { m += p.W; --q; }
+  else if (m >= p.W) { m -= p.W; ++q; }
 }
 
 // Clears the per-head counters that later kernels of the same call accumulate into.

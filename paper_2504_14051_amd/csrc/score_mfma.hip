@@ -99,7 +99,9 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
     for (int t = 0; t < kNBuf - 1 && t < ntiles; ++t) issue(t, t);
     // ---- per-row-group set-up: Q fragments, window positions, normalisers ----------
     for (int i = tid; i < ROWS; i += kThreads) {
-      iw_lds[i] = (rg0 + i) < p.R ? (rg0 + i) % p.W : -1;
+      int g_unused, iw_i;
+      divmod_w(p, rg0 + i, g_unused, iw_i);
+      iw_lds[i] = (rg0 + i) < p.R ? iw_i : -1;
       if (MODE == 1) lse_lds[i] = (rg0 + i) < p.R ? p.lse2[(int64_t)bh * p.Rp + rg0 + i] : INFINITY;
     }
     bf16x8 qf[RBW][8];
@@ -112,7 +114,8 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
       const int r = rbase + (lane & 31);
       m_run[rb] = -INFINITY; l_run[rb] = 0.f; nvis_row[rb] = 0;
       if (r < p.R) {
-        const int g = r / p.W, iw = r % p.W;
+        int g, iw;
+        divmod_w(p, r, g, iw);
         const unsigned char* qp = reinterpret_cast<const unsigned char*>(p.q) +
             ((int64_t)b * p.qsb + (int64_t)(hk * p.G + g) * p.qsh + (int64_t)iw * p.qsw) * 2 + (lane >> 5) * 16;
 #pragma unroll
@@ -140,16 +143,19 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
         const int kb = kw * KBW + kbi;                        // 32-key block inside the tile
         const int row = kb * 32 + (lane & 31);
         f32x16 acc[RBW];
+        bf16x8 kf[8];                                         // all eight K fragments first, so
+#pragma unroll                                                // that their LDS latencies overlap
+        for (int ks = 0; ks < 8; ++ks)
+          kf[ks] = __builtin_bit_cast(
+              bf16x8, *reinterpret_cast<const uint4*>(&Ks[buf][swz(row, 2 * ks + (lane >> 5))]));
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 kf = __builtin_bit_cast(
-              bf16x8, *reinterpret_cast<const uint4*>(&Ks[buf][swz(row, 2 * ks + (lane >> 5))]));
 #pragma unroll
           for (int rb = 0; rb < RBW; ++rb) {
             const f32x16 cin = ks == 0 ? f32x16{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f,
                                                 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f} : acc[rb];
-            if (MODE == 0) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[rb][ks], cin, 0, 0, 0);
-            else           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf, cin, 0, 0, 0);
+            if (MODE == 0) acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[rb][ks], cin, 0, 0, 0);
+            else           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf[ks], cin, 0, 0, 0);
           }
         }
         const int jb = tile0 + kb * 32;                       // first key of the block
@@ -166,9 +172,11 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
             for (int i = 1; i < 16; ++i) mx = __builtin_fmaxf(mx, acc[rb][i]);
             const float mn = __builtin_fmaxf(m_run[rb], mx * p.c2);     // c2 > 0
             if (!TAIL || mn > -INFINITY) {
-              float s = 0.f;
-#pragma unroll
-              for (int i = 0; i < 16; ++i) s += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[rb][i], p.c2, -mn));
+              float e[16];                                      // independent terms, then a tree:
+#pragma unroll                                                // no serial exp -> add chain
+              for (int i = 0; i < 16; ++i) e[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[rb][i], p.c2, -mn));
+              const float s = (((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]))) +
+                              (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15])));
               l_run[rb] = l_run[rb] * __builtin_amdgcn_exp2f(m_run[rb] - mn) + s;
               m_run[rb] = mn;
             }
@@ -179,6 +187,7 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
 #pragma unroll
           for (int rb = 0; rb < RBW; ++rb) {
             const int rl = (wr * RBW + rb) * 32;                // row offset inside the group
+            float e[16];                                        // independent terms, then a tree
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
               float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[rb][i], p.c2, -lse[rb][i]));
@@ -187,8 +196,10 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
                 const bool vis = j < N && iw >= 0 && (!p.wic || j < P + iw + 1);
                 pv = vis ? pv : 0.f;
               }
-              cs += pv;
+              e[i] = pv;
             }
+            cs += (((e[0] + e[1]) + (e[2] + e[3])) + ((e[4] + e[5]) + (e[6] + e[7]))) +
+                  (((e[8] + e[9]) + (e[10] + e[11])) + ((e[12] + e[13]) + (e[14] + e[15])));
           }
           cs += __shfl_xor(cs, 32, kWave);
           if (lane < 32) a_lds[abuf][wr][kb * 32 + lane] = cs;
