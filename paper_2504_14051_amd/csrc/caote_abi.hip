@@ -90,16 +90,21 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
     return len < lo ? lo : (len > hi ? hi : len);
   };
   p.use_mfma = p.dtype == CAOTE_BF16 && p.D == 128 && p.R > 16;
+  p.small_r = !p.use_mfma && p.R <= 8;
+  p.s_rows = p.R <= 4 ? 4 : 8;
   p.split_len = p.use_mfma ? chunk_len(512, 128, 1 << 20) : chunk_len(1024, 256, 8192);
   p.n_split = ceil_div(p.cap, p.split_len);
   p.vchunk_len = caote::kVChunk;
   p.n_vchunk = ceil_div(p.cap, p.vchunk_len);
+  p.vrep = ceil_div(p.cap, 128 * caote::kVChunk);      // at most 128 partial sums per head
+  p.n_vsum = ceil_div(p.n_vchunk, p.vrep);
   p.Rp = (int)align_up((size_t)p.R, 32);
 
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return ws ? ws + o : nullptr; };
   p.stats = (float*)carve((size_t)BH * p.n_split * p.Rp * 2 * sizeof(float));
   p.lse2 = (float*)carve((size_t)BH * p.Rp * sizeof(float));
+  p.S = (float*)carve(p.small_r ? (size_t)BH * p.cap * p.s_rows * sizeof(float) : 0);
   p.a = (float*)carve((size_t)BH * p.cap * sizeof(float));
   p.h = (float*)carve((size_t)BH * p.cap * sizeof(float));
   p.opart = (float*)carve((size_t)BH * p.n_vchunk * p.D * sizeof(float));
@@ -131,8 +136,9 @@ caote_status device_status(hipError_t e, const char* what) {
 }
 
 caote_status do_score(Params& p, hipStream_t s, caote::PhaseHook* hook = nullptr) {
-  hipError_t e = p.use_mfma ? caote::launch_score_mfma(p, s, hook)
-                            : caote::launch_score_generic(p, s, hook);
+  hipError_t e = p.use_mfma   ? caote::launch_score_mfma(p, s, hook)
+                 : p.small_r  ? caote::launch_score_small(p, s, hook)
+                              : caote::launch_score_generic(p, s, hook);
   if (e != hipSuccess) return device_status(e, "score (key sweeps)");
   return device_status(caote::launch_value_passes(p, s, hook), "score (value sweeps)");
 }

@@ -34,6 +34,8 @@ struct Params {
   // ---- workspace ----
   float* stats;       // [BH][n_split][Rp][2]  partial (max, sum) per query row
   float* lse2;        // [BH][Rp]              log2-sum-exp2 per query row
+  float* S;           // [BH][cap][s_rows]     stored logits (few-row path only)
+  int small_r, s_rows;// few-row path: R <= 8, logits kept instead of a second key sweep
   float* a;           // [BH][cap]             column sums of attention
   float* h;           // [BH][cap]             base score (aliases `base` for H2O)
   float* opart;       // [BH][n_vchunk][D]     partial sum of h_j v_j
@@ -47,6 +49,7 @@ struct Params {
   int hist_zeroed;    // an earlier kernel of this call has cleared `hist` (fused call)
   void* stage;        // compaction staging
   int n_split, split_len, Rp, n_vchunk, vchunk_len;
+  int vrep, n_vsum;   // value sum: 256-token chunks per workgroup, partial sums per head
   int use_mfma;       // key sweeps on the matrix cores (bf16, head_dim 128, R > 16)
 };
 
@@ -114,6 +117,8 @@ inline void mark(PhaseHook* h, const char* name) { if (h) h->mark(name); }
 
 hipError_t launch_score_generic(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_score_mfma(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_score_small(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook);

@@ -8,8 +8,8 @@
 // by a second kernel (stream order is the barrier).  Rows that already sit at their
 // rank are not touched.
 //
-// Evict-one sequences in SWAP_LAST mode move a single row: the last row drops into
-// the hole.  A sequence that evicts any other number of tokens is compacted stably.
+// Evict-one sequences in SWAP_LAST mode move a single row (k_swap_last): the last row drops
+// into the hole.  A sequence that evicts any other number of tokens is compacted stably.
 #include "common.hpp"
 
 namespace caote {
@@ -22,11 +22,40 @@ __device__ __forceinline__ int source_row(const Params& p, const int32_t* idx, i
   const int n_keep = min(N, p.budget);
   if (i >= n_keep) return -1;
   const int src = idx[i];
-  if (p.mode == CAOTE_COMPACT_SWAP_LAST && N - n_keep == 1) {
-    const bool first_hole = src != i && (i == 0 || idx[i - 1] == i - 1);
-    return first_hole ? N - 1 : -1;
-  }
+  if (p.mode == CAOTE_COMPACT_SWAP_LAST && N - n_keep == 1) return -1;   // k_swap_last's job
   return src == i ? -1 : src;
+}
+
+// Evict-one sequences in SWAP_LAST mode: the kept list is 0..N-2 with one index missing;
+// the last row drops into that hole.  One workgroup per (sequence, head); source and
+// destination are different rows, so no staging is needed.
+__global__ __launch_bounds__(kThreads) void k_swap_last(const Params p, int row_bytes) {
+  const int bh = blockIdx.x, b = bh / p.Hkv, hk = bh % p.Hkv;
+  const int N = seq_len(p, b);
+  const int n_keep = min(N, p.budget);
+  if (N - n_keep != 1) return;
+  const int32_t* idx = p.kept + (int64_t)bh * p.budget;
+  __shared__ int s_hole;
+  if (threadIdx.x == 0) s_hole = N - 1;                 // nothing missing below: the last row goes
+  __syncthreads();
+  for (int i = threadIdx.x; i < n_keep; i += kThreads)  // the first rank whose index is not its own
+    if (idx[i] != i && (i == 0 || idx[i - 1] == i - 1)) s_hole = i;
+  __syncthreads();
+  const int hole = s_hole;
+  if (hole == N - 1) return;
+  const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
+  char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
+  char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
+  const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
+  const int cpr = row_bytes / 16;
+  const int t = threadIdx.x;
+  if (t < cpr)
+    *reinterpret_cast<uint4*>(Kb + hole * krow + t * 16) = *reinterpret_cast<const uint4*>(Kb + (N - 1) * krow + t * 16);
+  else if (t < 2 * cpr)
+    *reinterpret_cast<uint4*>(Vb + hole * vrow + (t - cpr) * 16) =
+        *reinterpret_cast<const uint4*>(Vb + (N - 1) * vrow + (t - cpr) * 16);
+  else if (t == 2 * cpr && p.base)
+    p.base[(int64_t)bh * p.cap + hole] = p.base[(int64_t)bh * p.cap + N - 1];
 }
 
 // dir 0: cache -> staging, dir 1: staging -> cache.
@@ -72,6 +101,12 @@ hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int row_bytes = p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
   const int64_t chunks = (int64_t)p.budget * (row_bytes / 16);
   const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads), p.B * p.Hkv);
+  if (p.mode == CAOTE_COMPACT_SWAP_LAST) {
+    hipLaunchKernelGGL(k_swap_last, dim3(p.B * p.Hkv), dim3(kThreads), 0, s, p, row_bytes);
+    mark(hook, "compact_swap");
+    // with equal lengths and exactly one token over budget every sequence is an evict-one
+    if (p.seq_lens == nullptr && p.cap - p.budget == 1) return hipGetLastError();
+  }
   hipLaunchKernelGGL(k_move_rows<0>, grid, dim3(kThreads), 0, s, p, row_bytes);
   mark(hook, "compact_gather");
   hipLaunchKernelGGL(k_move_rows<1>, grid, dim3(kThreads), 0, s, p, row_bytes);

@@ -300,13 +300,22 @@ __global__ __launch_bounds__(kThreads) void k_merge_stats_wave(const Params p) {
   if (lane == 0) p.lse2[(int64_t)bh * p.Rp + r] = L > 0.f ? M + log2f(L) : INFINITY;
 }
 
+}  // namespace
+
+hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook) {
+  hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kThreads), 0, s, p);
+  mark(hook, "merge_stats");
+  return hipGetLastError();
+}
+
+namespace {
+
 template <int WR, int RBW>
 hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_split, p.B * p.Hkv);
   hipLaunchKernelGGL((k_logits_mfma<WR, RBW, 0>), grid, dim3(kThreads), 0, s, p);
   mark(hook, "key_rowstats");
-  hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kThreads), 0, s, p);
-  mark(hook, "merge_stats");
+  if (launch_merge_stats(p, s, hook) != hipSuccess) return hipGetLastError();
   hipLaunchKernelGGL((k_logits_mfma<WR, RBW, 1>), grid, dim3(kThreads), 0, s, p);
   mark(hook, "key_colsum");
   return hipGetLastError();

@@ -1,14 +1,16 @@
 // Value-side sweeps of the CAOTE score (Sec. 3.2 general form, Sec. 3.3 FastCAOTE).
 //
-//   k_vsum   : base score h from the column sums a (H2O accumulate / SnapKV max-pool),
-//              then partial sums  sum_j h_j v_j  and  sum_j h_j  per chunk of 256 tokens.
+//   k_vsum   : base score h from the attention mass a (H2O accumulate / SnapKV max-pool),
+//              then partial sums  sum_j h_j v_j  and  sum_j h_j  per workgroup (one or more
+//              chunks of 256 tokens).  On the few-row path a_j comes straight from the
+//              stored logits: a_j = sum_r exp2(t_rj - lse2_r).
 //   k_vfinal : adds the partials of a head up in chunk order (fixed order: the result
 //              does not depend on scheduling).
 //   k_vscore : o = (sum h_j v_j) / Z,  score_j = h_j / (Z - h_j) * ||v_j - o||_2.
 //
 // ||v_j - o|| is taken directly on the differences (not via ||v||^2 - 2 v.o + ||o||^2,
 // which cancels when v_j is close to o).  1 - w_j is formed as (Z - h_j) / Z.
-// Both kernels are HBM-bound streams over V: every thread keeps 8 independent 16-byte
+// Both sweeps are HBM-bound streams over V: every thread keeps 8 independent 16-byte
 // loads in flight, 16 lanes per 256-byte row.
 #include <float.h>
 
@@ -43,6 +45,23 @@ __device__ __forceinline__ void widen(const Frag<float>& f, float (&x)[8]) {
   x[4] = f.hi.x; x[5] = f.hi.y; x[6] = f.hi.z; x[7] = f.hi.w;
 }
 
+// Attention mass of token j (Sec. 2, f_score,j = sum_i A_ij): from the column sums of
+// the second key sweep, or, on the few-row path, from the stored logits.
+__device__ __forceinline__ float mass_of(const Params& p, int bh, int j, const float (&lse)[8]) {
+  if (!p.small_r) return p.a[(int64_t)bh * p.cap + j];
+  const float* t = p.S + ((int64_t)bh * p.cap + j) * p.s_rows;
+  float a = 0.f;
+  if (p.s_rows == 4) {
+    const float4 v = *reinterpret_cast<const float4*>(t);
+    a = (exp2f(v.x - lse[0]) + exp2f(v.y - lse[1])) + (exp2f(v.z - lse[2]) + exp2f(v.w - lse[3]));
+  } else {
+    const float4 v = *reinterpret_cast<const float4*>(t), w = *reinterpret_cast<const float4*>(t + 4);
+    a = ((exp2f(v.x - lse[0]) + exp2f(v.y - lse[1])) + (exp2f(v.z - lse[2]) + exp2f(v.w - lse[3]))) +
+        ((exp2f(w.x - lse[4]) + exp2f(w.y - lse[5])) + (exp2f(w.z - lse[6]) + exp2f(w.w - lse[7])));
+  }
+  return a;
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
   constexpr int TL = D / 8;
@@ -51,8 +70,8 @@ __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
   static_assert(ITER % kUnroll == 0, "chunk must be a whole number of unrolled groups");
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
-  const int c0 = blockIdx.x * kVChunk;
-  if (c0 >= N) return;
+  const int w0 = blockIdx.x * p.vrep * kVChunk;          // first token of this workgroup
+  if (w0 >= N) return;
   const int tid = threadIdx.x, team = tid / TL, tl = tid % TL;
   const int lo = min(p.ph, N), hi = max(lo, N - p.pt);   // scored rows [lo,hi)
   const int half = p.pool / 2;
@@ -61,53 +80,65 @@ __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
   __shared__ float red[RPI][D];
   __shared__ float zred[kThreads / kWave];
 
-  // ---- phase A: one thread per token: base score h_j --------------------------------
-  {
-    const float* a = p.a + (int64_t)bh * p.cap;
-    float* h = p.h + (int64_t)bh * p.cap;
-    const int j = c0 + tid;
-    float hj = 0.f;
-    bool scored = false;
-    if (j < N) {
-      scored = j >= lo && j < hi;
-      hj = a[j];
-      if (p.base_mode == CAOTE_BASE_H2O) {
-        hj += h[j];                           // h aliases the accumulator
-      } else if (p.base_mode == CAOTE_BASE_SNAPKV && scored) {
-        const int t0 = max(lo, j - half), t1 = min(hi - 1, j + half);
-        for (int t = t0; t <= t1; ++t) hj = fmaxf(hj, a[t]);
-      }
-      h[j] = hj;
-    }
-    w_lds[tid] = scored ? (p.variant == CAOTE_FAST ? 1.f : hj) : 0.f;
-    float z = scored ? hj : 0.f;
+  // few-row path: normalisers of the (at most 8) query rows; rows that do not exist or see
+  // no key have lse2 = +inf and stored logits -inf, both give exp2(-inf) = 0
+  float lse[8];
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) z += __shfl_xor(z, o, kWave);
-    if ((tid & 63) == 0) zred[tid >> 6] = z;
-  }
-  __syncthreads();
+  for (int r = 0; r < 8; ++r)
+    lse[r] = p.small_r && r < p.R ? p.lse2[(int64_t)bh * p.Rp + r] : INFINITY;
 
-  // ---- phase B: stream the chunk of V -------------------------------------------------
   const T* Vb = reinterpret_cast<const T*>(p.V) + (int64_t)b * p.vsb + (int64_t)hk * p.vsh + tl * 8;
+  float* h = p.h + (int64_t)bh * p.cap;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int it0 = 0; it0 < ITER; it0 += kUnroll) {
-    Frag<T> f[kUnroll];
-    float w[kUnroll];
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int rl = (it0 + u) * RPI + team;
-      w[u] = w_lds[rl];
-      if (w[u] != 0.f) fetch(Vb + (int64_t)(c0 + rl) * p.vsn, f[u]); else zero(f[u]);
+  float zsum = 0.f;
+
+  for (int rep = 0; rep < p.vrep; ++rep) {
+    const int c0 = w0 + rep * kVChunk;
+    if (c0 >= N) break;
+    // ---- phase A: one thread per token: base score h_j ------------------------------
+    {
+      const int j = c0 + tid;
+      float hj = 0.f;
+      bool scored = false;
+      if (j < N) {
+        scored = j >= lo && j < hi;
+        hj = mass_of(p, bh, j, lse);
+        if (p.base_mode == CAOTE_BASE_H2O) {
+          hj += h[j];                           // h aliases the accumulator
+        } else if (p.base_mode == CAOTE_BASE_SNAPKV && scored) {
+          const int t0 = max(lo, j - half), t1 = min(hi - 1, j + half);
+          for (int t = t0; t <= t1; ++t) hj = fmaxf(hj, t == j ? hj : mass_of(p, bh, t, lse));
+        }
+        h[j] = hj;
+      }
+      w_lds[tid] = scored ? (p.variant == CAOTE_FAST ? 1.f : hj) : 0.f;
+      zsum += scored ? hj : 0.f;
     }
+    __syncthreads();
+    // ---- phase B: stream the chunk of V -----------------------------------------------
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      float x[8];
-      widen(f[u], x);
+    for (int it0 = 0; it0 < ITER; it0 += kUnroll) {
+      Frag<T> f[kUnroll];
+      float w[kUnroll];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = fmaf(w[u], x[e], acc[e]);
+      for (int u = 0; u < kUnroll; ++u) {
+        const int rl = (it0 + u) * RPI + team;
+        w[u] = w_lds[rl];
+        if (w[u] != 0.f) fetch(Vb + (int64_t)(c0 + rl) * p.vsn, f[u]); else zero(f[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < kUnroll; ++u) {
+        float x[8];
+        widen(f[u], x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(w[u], x[e], acc[e]);
+      }
     }
+    __syncthreads();                        // w_lds is rewritten by the next chunk
   }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) zsum += __shfl_xor(zsum, o, kWave);
+  if ((tid & 63) == 0) zred[tid >> 6] = zsum;
 #pragma unroll
   for (int e = 0; e < 8; ++e) red[team][tl * 8 + e] = acc[e];
   __syncthreads();
@@ -115,28 +146,28 @@ __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
     float s = 0.f;
 #pragma unroll
     for (int t = 0; t < RPI; ++t) s += red[t][tid];
-    p.opart[((int64_t)bh * p.n_vchunk + blockIdx.x) * D + tid] = s;
+    p.opart[((int64_t)bh * p.n_vsum + blockIdx.x) * D + tid] = s;
   } else if (tid == D) {
     float z = 0.f;
 #pragma unroll
     for (int w = 0; w < kThreads / kWave; ++w) z += zred[w];
-    p.zpart[(int64_t)bh * p.n_vchunk + blockIdx.x] = z;
+    p.zpart[(int64_t)bh * p.n_vsum + blockIdx.x] = z;
   }
 }
 
-// Adds the per-chunk partial sums of one head up, in chunk order.
+// Adds the per-workgroup partial sums of one head up, in order.
 __global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
   const int bh = blockIdx.x, b = bh / p.Hkv;
   const int N = seq_len(p, b);
-  const int nch = (N + kVChunk - 1) / kVChunk;
+  const int nch = (N + p.vrep * kVChunk - 1) / (p.vrep * kVChunk);
   const int tid = threadIdx.x, D = p.D;
-  // kFinalThreads / 128 chunk groups x 128 columns; group g takes chunks g, g+G, ...
+  // kFinalThreads / 128 groups x 128 columns; group g takes partials g, g+G, ...
   constexpr int G = kFinalThreads / kMaxD;
   const int g = tid / kMaxD, col = tid % kMaxD;
   __shared__ float red[G][kMaxD + 1];
   float s = 0.f, z = 0.f;
   if (col < D) {
-    const float* op = p.opart + (int64_t)bh * p.n_vchunk * D + col;
+    const float* op = p.opart + (int64_t)bh * p.n_vsum * D + col;
     int c = g;
     for (; c + 3 * G < nch; c += 4 * G) {                     // four independent loads in flight
       const float x0 = op[(int64_t)c * D], x1 = op[(int64_t)(c + G) * D];
@@ -146,7 +177,7 @@ __global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
     for (; c < nch; c += G) s += op[(int64_t)c * D];
   }
   if (col == 0) {
-    const float* zp = p.zpart + (int64_t)bh * p.n_vchunk;
+    const float* zp = p.zpart + (int64_t)bh * p.n_vsum;
     for (int c = g; c < nch; c += G) z += zp[c];
     red[g][kMaxD] = z;
   }
@@ -204,7 +235,7 @@ __global__ __launch_bounds__(kThreads) void k_vscore(const Params p) {
     }
   }
   __syncthreads();
-  // ---- one thread per token: the score, and its histogram bin ---------------------------
+  // ---- one thread per token: the score ------------------------------------------------------
   const int j = c0 + tid;
   if (j >= N) return;
   float out = INFINITY;
@@ -217,12 +248,12 @@ __global__ __launch_bounds__(kThreads) void k_vscore(const Params p) {
 
 template <typename T, int D>
 hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
-  const dim3 grid(p.n_vchunk, p.B * p.Hkv);
-  hipLaunchKernelGGL((k_vsum<T, D>), grid, dim3(kThreads), 0, s, p);
+  const int bh = p.B * p.Hkv;
+  hipLaunchKernelGGL((k_vsum<T, D>), dim3(p.n_vsum, bh), dim3(kThreads), 0, s, p);
   mark(hook, "value_sum");
-  hipLaunchKernelGGL(k_vfinal, dim3(p.B * p.Hkv), dim3(kFinalThreads), 0, s, p);
+  hipLaunchKernelGGL(k_vfinal, dim3(bh), dim3(kFinalThreads), 0, s, p);
   mark(hook, "value_final");
-  hipLaunchKernelGGL((k_vscore<T, D>), grid, dim3(kThreads), 0, s, p);
+  hipLaunchKernelGGL((k_vscore<T, D>), dim3(p.n_vchunk, bh), dim3(kThreads), 0, s, p);
   mark(hook, "value_score");
   return hipGetLastError();
 }
