@@ -24,7 +24,6 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int kThreads = 256;
 constexpr int kTN = 64;                 // keys per LDS tile
 constexpr int kD = 128;
 constexpr int kRowBytes = kD * 2;       // 256
@@ -51,9 +50,11 @@ __device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes 
 // dimension (sweep 1); also the row index when rows are the M dimension (sweep 2).
 __device__ __forceinline__ int m_of(int i, int lane) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
 
-template <int WR, int RBW, int MODE>
-__global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
-  constexpr int WK = 4 / WR;            // key waves
+template <int NWV, int WR, int RBW, int MODE>
+__global__ __launch_bounds__(NWV * kWave) void k_logits_mfma(const Params p) {
+  constexpr int kThreads = NWV * kWave; // NWV waves = WR row waves x WK key waves
+  constexpr int LPT = 16 / NWV;         // 1 KiB loads per wave per K tile
+  constexpr int WK = NWV / WR;          // key waves
   constexpr int KBW = (kTN / 32) / WK;  // 32-key blocks per wave per tile
   constexpr int ROWS = WR * RBW * 32;   // query rows per row group
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
@@ -85,12 +86,12 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
     // side: the lane that owns slot (row, pc) fetches chunk pc ^ (row & 15) of that row.
     auto issue = [&](int t, int buf) {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int slot = (wave * 4 + u) * kWave + lane;      // 16-byte slot inside the tile
+      for (int u = 0; u < LPT; ++u) {
+        const int slot = (wave * LPT + u) * kWave + lane;    // 16-byte slot inside the tile
         const int row = slot / kChunks, pc = slot % kChunks;
         const int j = min(c0 + t * kTN + row, N - 1);        // rows past the end repeat the last one
         load_to_lds16(Kb + j * krow + ((pc ^ (row & 15)) << 4),
-                      __builtin_amdgcn_readfirstlane(lds_addr(&Ks[buf][(wave * 4 + u) * kWave * 16])));
+                      __builtin_amdgcn_readfirstlane(lds_addr(&Ks[buf][(wave * LPT + u) * kWave * 16])));
       }
     };
     // The first two K tiles are requested before anything else, so that their latency
@@ -236,7 +237,7 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
     for (int t = 0; t < ntiles; ++t) {
       // this wave's share of tile t has landed once at most the 4 loads of tile t+1 are
       // still in flight (loads complete in order; a store in between cannot hide a load)
-      if (t + 1 < ntiles) wait_vmcnt<4>(); else wait_vmcnt<0>();
+      if (t + 1 < ntiles) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
       __syncthreads();                   // ... and so has everyone else's; tile t-1 is done with
       if (t > 0) flush_a(t - 1, (t - 1) & 1);
       if (t + kNBuf - 1 < ntiles) issue(t + kNBuf - 1, buf == 0 ? kNBuf - 1 : buf - 1);
@@ -277,10 +278,11 @@ __global__ __launch_bounds__(kThreads) void k_logits_mfma(const Params p) {
 }
 
 // lse2_r = log2 sum_j exp2(t_rj): one wave per query row, lanes stride over the splits.
-__global__ __launch_bounds__(kThreads) void k_merge_stats_wave(const Params p) {
+constexpr int kMergeThreads = 256;
+__global__ __launch_bounds__(kMergeThreads) void k_merge_stats_wave(const Params p) {
   const int bh = blockIdx.y, b = bh / p.Hkv;
   if (blockIdx.x == 0) reset_counters(p, bh);
-  const int r = blockIdx.x * (kThreads / kWave) + (threadIdx.x >> 6);
+  const int r = blockIdx.x * (kMergeThreads / kWave) + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (r >= p.R) return;
   const int N = seq_len(p, b);
@@ -303,20 +305,20 @@ __global__ __launch_bounds__(kThreads) void k_merge_stats_wave(const Params p) {
 }  // namespace
 
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook) {
-  hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kThreads), 0, s, p);
+  hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kMergeThreads), 0, s, p);
   mark(hook, "merge_stats");
   return hipGetLastError();
 }
 
 namespace {
 
-template <int WR, int RBW>
+template <int NWV, int WR, int RBW>
 hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_split, p.B * p.Hkv);
-  hipLaunchKernelGGL((k_logits_mfma<WR, RBW, 0>), grid, dim3(kThreads), 0, s, p);
+  hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid, dim3(NWV * kWave), 0, s, p);
   mark(hook, "key_rowstats");
   if (launch_merge_stats(p, s, hook) != hipSuccess) return hipGetLastError();
-  hipLaunchKernelGGL((k_logits_mfma<WR, RBW, 1>), grid, dim3(kThreads), 0, s, p);
+  hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 1>), grid, dim3(NWV * kWave), 0, s, p);
   mark(hook, "key_colsum");
   return hipGetLastError();
 }
@@ -326,9 +328,9 @@ hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
 // Requires: bf16, head_dim 128, split_len a multiple of 64.
 hipError_t launch_score_mfma(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int nrb = (p.R + 31) / 32;
-  if (nrb <= 2) return launch_cfg<2, 1>(p, s, hook);
-  if (nrb <= 4) return launch_cfg<2, 2>(p, s, hook);
-  return launch_cfg<4, 2>(p, s, hook);
+  if (nrb <= 2) return launch_cfg<4, 2, 1>(p, s, hook);
+  if (nrb <= 4) return launch_cfg<4, 2, 2>(p, s, hook);
+  return launch_cfg<8, 4, 2>(p, s, hook);
 }
 
 }  // namespace caote
