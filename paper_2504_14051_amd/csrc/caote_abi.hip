@@ -99,6 +99,9 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.vrep = ceil_div(p.cap, 128 * caote::kVChunk);      // at most 128 partial sums per head
   p.n_vsum = ceil_div(p.n_vchunk, p.vrep);
   p.Rp = (int)align_up((size_t)p.R, 32);
+  p.halo = p.base_mode == CAOTE_BASE_SNAPKV ? p.pool / 2 : 0;
+  p.fuse_v = p.use_mfma && p.halo <= 64;
+  p.n_vpart = p.fuse_v ? p.n_split : p.n_vsum;
 
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return ws ? ws + o : nullptr; };
@@ -107,8 +110,8 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.S = (float*)carve(p.small_r ? (size_t)BH * p.cap * p.s_rows * sizeof(float) : 0);
   p.a = (float*)carve((size_t)BH * p.cap * sizeof(float));
   p.h = (float*)carve((size_t)BH * p.cap * sizeof(float));
-  p.opart = (float*)carve((size_t)BH * p.n_vchunk * p.D * sizeof(float));
-  p.zpart = (float*)carve((size_t)BH * p.n_vchunk * sizeof(float));
+  p.opart = (float*)carve((size_t)BH * p.n_vpart * p.D * sizeof(float));
+  p.zpart = (float*)carve((size_t)BH * p.n_vpart * sizeof(float));
   p.osum = (float*)carve((size_t)BH * (caote::kMaxD + 1) * sizeof(float));
   p.hist = (uint32_t*)carve((size_t)BH * caote::kHistBins * sizeof(uint32_t));
   p.n_span = ceil_div(p.cap, caote::kSelSpan);

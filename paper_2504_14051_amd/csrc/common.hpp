@@ -38,8 +38,8 @@ struct Params {
   int small_r, s_rows;// few-row path: R <= 8, logits kept instead of a second key sweep
   float* a;           // [BH][cap]             column sums of attention
   float* h;           // [BH][cap]             base score (aliases `base` for H2O)
-  float* opart;       // [BH][n_vchunk][D]     partial sum of h_j v_j
-  float* zpart;       // [BH][n_vchunk]        partial sum of h_j
+  float* opart;       // [BH][n_vpart][D]      partial sum of h_j v_j
+  float* zpart;       // [BH][n_vpart]         partial sum of h_j
   float* osum;        // [BH][kMaxD+1]         sum h_j v_j (un-normalised) and, last, Z
   uint32_t* hist;     // [BH][kHistBins]       histogram of the score keys
   uint32_t* sel_cand; // [BH][cap]             keys of the threshold bin, one list per span
@@ -51,6 +51,9 @@ struct Params {
   int n_split, split_len, Rp, n_vchunk, vchunk_len;
   int vrep, n_vsum;   // value sum: 256-token chunks per workgroup, partial sums per head
   int use_mfma;       // key sweeps on the matrix cores (bf16, head_dim 128, R > 16)
+  int halo;           // SnapKV: pooling half-width (0 otherwise)
+  int fuse_v;         // the second key sweep also forms the value partial sums (one per split)
+  int n_vpart;        // partial sums per head in opart / zpart: n_split if fuse_v, else n_vsum
 };
 
 __device__ __forceinline__ int seq_len(const Params& p, int b) {

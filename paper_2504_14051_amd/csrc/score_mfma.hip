@@ -38,6 +38,11 @@ __device__ __forceinline__ void load_to_lds16(const void* gaddr, uint32_t lds_ba
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                : : "v"(gaddr), "s"(lds_base) : "memory", "m0");
 }
+// The 4-byte form: lane L fills lds_base + 4 L.
+__device__ __forceinline__ void load_to_lds4(const void* gaddr, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+               : : "v"(gaddr), "s"(lds_base) : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
@@ -51,12 +56,14 @@ __device__ __forceinline__ int swz(int row, int chunk) { return row * kRowBytes 
 __device__ __forceinline__ int m_of(int i, int lane) { return 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3); }
 
 template <int NWV, int WR, int RBW, int MODE>
-__global__ __launch_bounds__(NWV * kWave) void k_logits_mfma(const Params p) {
+__global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) {
   constexpr int kThreads = NWV * kWave; // NWV waves = WR row waves x WK key waves
   constexpr int LPT = 16 / NWV;         // 1 KiB loads per wave per K tile
   constexpr int WK = NWV / WR;          // key waves
   constexpr int KBW = (kTN / 32) / WK;  // 32-key blocks per wave per tile
   constexpr int ROWS = WR * RBW * 32;   // query rows per row group
+  constexpr bool COLSUM = MODE >= 1;    // sweep 2
+  constexpr bool FUSE = MODE == 2;      // sweep 2 that also accumulates sum_j h_j v_j
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
   const int c0 = blockIdx.x * p.split_len;
@@ -72,6 +79,12 @@ __global__ __launch_bounds__(NWV * kWave) void k_logits_mfma(const Params p) {
   __shared__ int iw_lds[ROWS];          // window position of each row of the group
   __shared__ float lse_lds[ROWS];       // sweep 2: normaliser of each row of the group
   __shared__ float st_lds[WK][ROWS][2];
+  // FUSE: attention mass of the last four tiles, weight of each row of the last four value
+  // steps, the H2O accumulator rows of two steps, and one tile of V rows
+  __shared__ float af[FUSE ? 4 * kTN : 1];
+  __shared__ float hw[FUSE ? 4 * kTN : 1];
+  __shared__ float bs[2][FUSE ? kTN : 1];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[FUSE ? kTN * kRowBytes : 16];
 
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.K) +
                             ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * 2;
@@ -103,7 +116,7 @@ __global__ __launch_bounds__(NWV * kWave) void k_logits_mfma(const Params p) {
       int g_unused, iw_i;
       divmod_w(p, rg0 + i, g_unused, iw_i);
       iw_lds[i] = (rg0 + i) < p.R ? iw_i : -1;
-      if (MODE == 1) lse_lds[i] = (rg0 + i) < p.R ? p.lse2[(int64_t)bh * p.Rp + rg0 + i] : INFINITY;
+      if (COLSUM) lse_lds[i] = (rg0 + i) < p.R ? p.lse2[(int64_t)bh * p.Rp + rg0 + i] : INFINITY;
     }
     bf16x8 qf[RBW][8];
     float lse[RBW][16];
@@ -128,7 +141,7 @@ __global__ __launch_bounds__(NWV * kWave) void k_logits_mfma(const Params p) {
         for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
       }
     }
-    if (MODE == 1) {
+    if (COLSUM) {
       __syncthreads();
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb)
@@ -212,14 +225,91 @@ __global__ __launch_bounds__(NWV * kWave) void k_logits_mfma(const Params p) {
       if (tile0 + kTN > min(P, N)) tile(std::true_type{}, buf, abuf, tile0);
       else                         tile(std::false_type{}, buf, abuf, tile0);
     };
-    auto flush_a = [&](int t, int buf) {                     // after the barrier of step t
+    // ---- FUSE: the value sum rides along (Sec. 3.2: o = sum_j w_j v_j) ---------------------
+    // Value step s covers the 64 keys c0 + 64 s - halo ... (shifted down by the pooling
+    // half-width, so that every neighbour it needs belongs to tiles <= s).  The first wave
+    // weighs its keys right after it has reduced the column sums of tile s (iteration s+1);
+    // the V rows come straight into LDS like the K tiles, requested in iteration s+1 as well,
+    // and every wave adds up the rows it fetched itself in iteration s+2.  Keys within `halo`
+    // of a chunk boundary need a neighbouring workgroup's column sums and are left to the
+    // kernel that adds the partial sums up.
+    const bool vlast = FUSE && rg0 + ROWS >= p.R;           // column sums are final in this group
+    constexpr int RW = LPT * 4;                             // value rows per wave per step
+    const int halo = p.halo;
+    const int lo = min(p.ph, N), hi = max(lo, N - p.pt);   // scored rows [lo,hi)
+    float vacc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float vz = 0.f;
+    auto flush_a = [&](int t, int buf) {                     // after the barrier of step t+1
       const int tile0 = c0 + t * kTN;
-      if (MODE == 1 && tid < kTN && tile0 + tid < c1) {
+      if (COLSUM && tid < kTN) {
         float s = 0.f;
+        if (tile0 + tid < c1) {
 #pragma unroll
-        for (int w = 0; w < WR; ++w) s += a_lds[buf][w][tid];
-        if (rg0 == 0) a_out[tile0 + tid] = s;
-        else a_out[tile0 + tid] += s;                          // later row groups add on
+          for (int w = 0; w < WR; ++w) s += a_lds[buf][w][tid];
+          if (rg0 > 0) s += a_out[tile0 + tid];                // later row groups add on
+          a_out[tile0 + tid] = s;
+        }
+        if (vlast) {
+          af[(t & 3) * kTN + tid] = s;
+          // base score and weight of key tid of value step t (same wave: the LDS writes above
+          // are visible to the reads below without a barrier)
+          const int j = tile0 - halo + tid;
+          const bool mine = j >= c0 + halo && j < c1 - halo;
+          const bool scored = mine && j >= lo && j < hi;
+          float hj = 0.f;
+          if (mine) {
+            hj = af[(j - c0) & (4 * kTN - 1)];
+            if (p.base_mode == CAOTE_BASE_H2O) {
+              hj += bs[t & 1][tid];
+            } else if (p.base_mode == CAOTE_BASE_SNAPKV && scored) {
+              const int t0 = max(lo, j - halo), t1 = min(hi - 1, j + halo);
+              for (int tt = t0; tt <= t1; ++tt) hj = fmaxf(hj, af[(tt - c0) & (4 * kTN - 1)]);
+            }
+            p.h[(int64_t)bh * p.cap + j] = hj;
+          }
+          hw[(t & 3) * kTN + tid] = scored ? (p.variant == CAOTE_FAST ? 1.f : hj) : 0.f;
+          vz += scored ? hj : 0.f;
+        }
+      }
+    };
+    const unsigned char* Vb = reinterpret_cast<const unsigned char*>(p.V) +
+                              ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * 2;
+    const int64_t vrow = p.vsn * 2;
+    const int jrow = c0 - halo + wave * RW + (lane >> 4);    // this lane's row of step 0, u = 0
+    const unsigned char* vlane = Vb + (int64_t)jrow * vrow + ((lane & 15) << 4);
+    auto v_issue = [&](int s, unsigned char* vs) {
+      const int j0 = jrow + s * kTN;
+      if (j0 - (lane >> 4) >= 0 && j0 - (lane >> 4) + RW <= N) {   // wave-uniform: no clamping
+        const unsigned char* ps = vlane + (int64_t)(s * kTN) * vrow;
+#pragma unroll
+        for (int u = 0; u < LPT; ++u)
+          load_to_lds16(ps + u * 4 * vrow, __builtin_amdgcn_readfirstlane(lds_addr(vs + (wave * LPT + u) * kWave * 16)));
+      } else {
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+          const int j = min(max(j0 + u * 4, 0), N - 1);
+          load_to_lds16(Vb + j * vrow + ((lane & 15) << 4),
+                        __builtin_amdgcn_readfirstlane(lds_addr(vs + (wave * LPT + u) * kWave * 16)));
+        }
+      }
+    };
+    auto base_issue = [&](int s) {                           // first wave: H2O accumulator rows of step s
+      const int j = min(max(c0 + s * kTN - halo + lane, 0), N - 1);
+      load_to_lds4(p.base + (int64_t)bh * p.cap + j, __builtin_amdgcn_readfirstlane(lds_addr(&bs[s & 1][0])));
+    };
+    auto v_consume = [&](int s, const unsigned char* vs) {
+#pragma unroll
+      for (int u = 0; u < LPT; ++u) {
+        const float w = hw[(s & 3) * kTN + wave * RW + u * 4 + (lane >> 4)];
+        const uint4 raw = *reinterpret_cast<const uint4*>(vs + ((wave * LPT + u) * kWave + lane) * 16);
+        vacc[0] = fmaf(w, __uint_as_float(raw.x << 16), vacc[0]);
+        vacc[1] = fmaf(w, __uint_as_float(raw.x & 0xffff0000u), vacc[1]);
+        vacc[2] = fmaf(w, __uint_as_float(raw.y << 16), vacc[2]);
+        vacc[3] = fmaf(w, __uint_as_float(raw.y & 0xffff0000u), vacc[3]);
+        vacc[4] = fmaf(w, __uint_as_float(raw.z << 16), vacc[4]);
+        vacc[5] = fmaf(w, __uint_as_float(raw.z & 0xffff0000u), vacc[5]);
+        vacc[6] = fmaf(w, __uint_as_float(raw.w << 16), vacc[6]);
+        vacc[7] = fmaf(w, __uint_as_float(raw.w & 0xffff0000u), vacc[7]);
       }
     };
     // Make the compiler finish its own global loads (Q fragments, normalisers) here: a wait
@@ -228,24 +318,63 @@ __global__ __launch_bounds__(NWV * kWave) void k_logits_mfma(const Params p) {
     for (int rb = 0; rb < RBW; ++rb) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qf[rb][ks]));
-      if (MODE == 1) {
+      if (COLSUM) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) asm volatile("" : : "v"(lse[rb][i]));
       }
     }
+    if (vlast && p.base_mode == CAOTE_BASE_H2O && wave == 0) base_issue(0);
     int buf = 0;
     for (int t = 0; t < ntiles; ++t) {
-      // this wave's share of tile t has landed once at most the 4 loads of tile t+1 are
-      // still in flight (loads complete in order; a store in between cannot hide a load)
+      // this wave's share of tile t has landed once at most the LPT loads of tile t+1 are
+      // still in flight (loads complete in order; a store in between cannot hide a load);
+      // so have the V rows requested in the last iteration, which are older than those
       if (t + 1 < ntiles) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
       __syncthreads();                   // ... and so has everyone else's; tile t-1 is done with
       if (t > 0) flush_a(t - 1, (t - 1) & 1);
-      if (t + kNBuf - 1 < ntiles) issue(t + kNBuf - 1, buf == 0 ? kNBuf - 1 : buf - 1);
+      const int spare = buf == 0 ? kNBuf - 1 : buf - 1;     // ring slot of tile t-1
+      if (vlast) {
+        if (t >= 2) v_consume(t - 2, Vs);
+        if (t >= 1) v_issue(t - 1, Vs);
+        if (p.base_mode == CAOTE_BASE_H2O && wave == 0 && t + 1 < ntiles) base_issue(t + 1);
+        // the last tile's V rows go where the K tile t+2 would have gone
+        if (t == ntiles - 1) v_issue(t, &Ks[spare][0]);
+      }
+      if (t + kNBuf - 1 < ntiles) issue(t + kNBuf - 1, spare);
       math(t, buf, t & 1);
       buf = buf + 1 == kNBuf ? 0 : buf + 1;
     }
+    if (vlast) wait_vmcnt<0>();
     __syncthreads();
     flush_a(ntiles - 1, (ntiles - 1) & 1);
+    if (vlast) {
+      if (ntiles >= 2) v_consume(ntiles - 2, Vs);
+      __syncthreads();                   // the weights of the last step are in LDS
+      v_consume(ntiles - 1, &Ks[(ntiles + 1) % kNBuf][0]);
+      // partial sums of this chunk: over the four teams of a wave, then over the waves
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        vacc[e] += __shfl_xor(vacc[e], 16, kWave);
+        vacc[e] += __shfl_xor(vacc[e], 32, kWave);
+      }
+#pragma unroll
+      for (int o = 32; o >= 1; o >>= 1) vz += __shfl_xor(vz, o, kWave);
+      __shared__ float red[NWV][kD + 4];
+      if (lane < 16) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = vacc[e];
+        if (tid == 0) red[0][kD] = vz;
+      }
+      __syncthreads();
+      if (tid < kD) {
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NWV; ++w) sum += red[w][tid];
+        p.opart[((int64_t)bh * p.n_vpart + blockIdx.x) * kD + tid] = sum;
+      } else if (tid == kD) {
+        p.zpart[(int64_t)bh * p.n_vpart + blockIdx.x] = red[0][kD];
+      }
+    }
     // ---- end of sweep 1: merge the two half-waves, then the key waves ------------------
     if (MODE == 0) {
 #pragma unroll
@@ -318,7 +447,8 @@ hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
   hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid, dim3(NWV * kWave), 0, s, p);
   mark(hook, "key_rowstats");
   if (launch_merge_stats(p, s, hook) != hipSuccess) return hipGetLastError();
-  hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 1>), grid, dim3(NWV * kWave), 0, s, p);
+  if (p.fuse_v) hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 2>), grid, dim3(NWV * kWave), 0, s, p);
+  else          hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 1>), grid, dim3(NWV * kWave), 0, s, p);
   mark(hook, "key_colsum");
   return hipGetLastError();
 }

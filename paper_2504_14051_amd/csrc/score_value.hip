@@ -146,28 +146,34 @@ __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
     float s = 0.f;
 #pragma unroll
     for (int t = 0; t < RPI; ++t) s += red[t][tid];
-    p.opart[((int64_t)bh * p.n_vsum + blockIdx.x) * D + tid] = s;
+    p.opart[((int64_t)bh * p.n_vpart + blockIdx.x) * D + tid] = s;
   } else if (tid == D) {
     float z = 0.f;
 #pragma unroll
     for (int w = 0; w < kThreads / kWave; ++w) z += zred[w];
-    p.zpart[(int64_t)bh * p.n_vsum + blockIdx.x] = z;
+    p.zpart[(int64_t)bh * p.n_vpart + blockIdx.x] = z;
   }
 }
 
-// Adds the per-workgroup partial sums of one head up, in order.
+// Adds the per-workgroup partial sums of one head up, in order.  When the second key sweep
+// formed the partial sums (one per split), the tokens within the pooling half-width of a
+// split boundary are still open: their pooled base score needs column sums of two splits.
+// They are few (2 * halo per split) and are finished here, from the column sums in memory.
 __global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
-  const int bh = blockIdx.x, b = bh / p.Hkv;
+  const int bh = blockIdx.x, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
-  const int nch = (N + p.vrep * kVChunk - 1) / (p.vrep * kVChunk);
+  const int part_len = p.fuse_v ? p.split_len : p.vrep * kVChunk;
+  const int nch = (N + part_len - 1) / part_len;
   const int tid = threadIdx.x, D = p.D;
   // kFinalThreads / 128 groups x 128 columns; group g takes partials g, g+G, ...
   constexpr int G = kFinalThreads / kMaxD;
+  constexpr int NW = kFinalThreads / kWave;
   const int g = tid / kMaxD, col = tid % kMaxD;
   __shared__ float red[G][kMaxD + 1];
+  __shared__ float edge[NW][kMaxD + 1];
   float s = 0.f, z = 0.f;
   if (col < D) {
-    const float* op = p.opart + (int64_t)bh * p.n_vsum * D + col;
+    const float* op = p.opart + (int64_t)bh * p.n_vpart * D + col;
     int c = g;
     for (; c + 3 * G < nch; c += 4 * G) {                     // four independent loads in flight
       const float x0 = op[(int64_t)c * D], x1 = op[(int64_t)(c + G) * D];
@@ -177,16 +183,85 @@ __global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
     for (; c < nch; c += G) s += op[(int64_t)c * D];
   }
   if (col == 0) {
-    const float* zp = p.zpart + (int64_t)bh * p.n_vsum;
+    const float* zp = p.zpart + (int64_t)bh * p.n_vpart;
     for (int c = g; c < nch; c += G) z += zp[c];
     red[g][kMaxD] = z;
   }
   red[g][col] = s;
+  const bool edges = p.fuse_v && p.halo > 0;    // bf16, head_dim 128: 16 lanes per value row
+  if (edges) {
+    const int team = tid >> 4, tl = tid & 15, halo = p.halo;
+    const int lo = min(p.ph, N), hi = max(lo, N - p.pt);
+    const float* a = p.a + (int64_t)bh * p.cap;
+    const bf16_t* Vb = reinterpret_cast<const bf16_t*>(p.V) + (int64_t)b * p.vsb + (int64_t)hk * p.vsh + tl * 8;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float zz = 0.f;
+    // kEdgeBatch tokens per team at a time, all their loads requested before the first use:
+    // the 16 lanes share the pooling window between them, and the value row does not wait
+    // for the weight, so a batch costs one round trip to memory
+    constexpr int kEdgeBatch = 4, kTeams = kFinalThreads / 16;
+    const int n_edge = nch * 2 * halo;
+    for (int idx0 = team; idx0 < n_edge; idx0 += kTeams * kEdgeBatch) {
+      int jj[kEdgeBatch];
+      bool sc[kEdgeBatch];
+      float hj[kEdgeBatch], x[kEdgeBatch][8];
+#pragma unroll
+      for (int u = 0; u < kEdgeBatch; ++u) {
+        const int idx = idx0 + u * kTeams;
+        const int sp = idx / (2 * halo), o = idx - sp * 2 * halo;
+        const int c0 = sp * p.split_len, c1 = min(N, c0 + p.split_len);
+        const int j = o < halo ? c0 + o : c1 - 2 * halo + o;
+        // front edge: the first `halo` tokens of the split; back edge: the last `halo`, unless
+        // the split is so short that the front edge already covers them
+        const bool valid = idx < n_edge && (o < halo ? j < c1 : j - c0 >= halo);
+        jj[u] = valid ? j : -1;
+        sc[u] = valid && j >= lo && j < hi;
+        hj[u] = -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[u][e] = 0.f;
+        if (valid) {
+          hj[u] = a[j];
+          if (sc[u]) {
+            load8(Vb + (int64_t)j * p.vsn, x[u]);
+            const int t0 = max(lo, j - halo), t1 = min(hi - 1, j + halo);
+            for (int t = t0 + tl; t <= t1; t += 16) hj[u] = fmaxf(hj[u], a[t]);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kEdgeBatch; ++u) {
+#pragma unroll
+        for (int m = 8; m >= 1; m >>= 1) hj[u] = fmaxf(hj[u], __shfl_xor(hj[u], m, kWave));
+        if (jj[u] >= 0 && tl == 0) p.h[(int64_t)bh * p.cap + jj[u]] = hj[u];
+        const float w = sc[u] ? (p.variant == CAOTE_FAST ? 1.f : hj[u]) : 0.f;
+        if (tl == 0) zz += sc[u] ? hj[u] : 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(w, x[u][e], acc[e]);
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      acc[e] += __shfl_xor(acc[e], 16, kWave);
+      acc[e] += __shfl_xor(acc[e], 32, kWave);
+    }
+    zz += __shfl_xor(zz, 16, kWave);
+    zz += __shfl_xor(zz, 32, kWave);
+    const int lane = tid & 63, wave = tid >> 6;
+    if (lane < 16) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) edge[wave][lane * 8 + e] = acc[e];
+      if (lane == 0) edge[wave][kMaxD] = zz;
+    }
+  }
   __syncthreads();
   if (tid <= kMaxD) {
     float t = 0.f;
 #pragma unroll
     for (int i = 0; i < G; ++i) t += red[i][tid];
+    if (edges) {
+#pragma unroll
+      for (int i = 0; i < NW; ++i) t += edge[i][tid];
+    }
     p.osum[(int64_t)bh * (kMaxD + 1) + tid] = t;
   }
 }
@@ -249,8 +324,10 @@ __global__ __launch_bounds__(kThreads) void k_vscore(const Params p) {
 template <typename T, int D>
 hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int bh = p.B * p.Hkv;
-  hipLaunchKernelGGL((k_vsum<T, D>), dim3(p.n_vsum, bh), dim3(kThreads), 0, s, p);
-  mark(hook, "value_sum");
+  if (!p.fuse_v) {
+    hipLaunchKernelGGL((k_vsum<T, D>), dim3(p.n_vsum, bh), dim3(kThreads), 0, s, p);
+    mark(hook, "value_sum");
+  }
   hipLaunchKernelGGL(k_vfinal, dim3(bh), dim3(kFinalThreads), 0, s, p);
   mark(hook, "value_final");
   hipLaunchKernelGGL((k_vscore<T, D>), dim3(p.n_vchunk, bh), dim3(kThreads), 0, s, p);
