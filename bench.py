@@ -40,8 +40,9 @@ def algorithmic_bytes(wl, n_tokens=None):
     return {"kv": kv, "q": q, "vectors": vec, "compact": comp, "total": kv + q + vec + comp}
 
 
-def phase_bytes(wl, name):
-    """Compulsory HBM bytes of one kernel of the path, given that its inputs live in HBM."""
+def phase_bytes(wl, name, fused_value_sum=False):
+    """Compulsory HBM bytes of one kernel of the path, given that its inputs live in HBM.
+    fused_value_sum: the second key sweep also streams V once (no separate value_sum kernel)."""
     N, d, esz = wl.context, wl.head_dim, (2 if wl.dtype == "bf16" else 4)
     bh = wl.batch * wl.n_kv_heads
     R = wl.group * wl.window
@@ -52,12 +53,17 @@ def phase_bytes(wl, name):
     table = {
         "key_rowstats": k_bytes + q_bytes,
         "merge_stats": bh * R * 8,
-        "key_colsum": k_bytes + q_bytes + vec,
+        "key_colsum": k_bytes + q_bytes + vec + ((k_bytes + vec) if fused_value_sum else 0),
         "key_sweeps": k_bytes + q_bytes + vec,          # fused: K from HBM once
         "value_sum": k_bytes + 2 * vec,
         "value_score": k_bytes + 2 * vec,
         "value_sweeps": k_bytes + 3 * vec,
+        "value_final": bh * (d + 1) * 4 * 2,              # at least: one partial sum in, the total out
         "select": vec + bh * wl.budget * 4,
+        "select_hist": vec,
+        "select_span": vec,
+        "select_emit": vec + bh * wl.budget * 4,
+        "compact_swap": bh * 2 * 2 * d * esz,            # one row of K and of V read and written per head
         "compact_gather": 2 * 2 * rows,
         "compact_scatter": 2 * 2 * rows,
         "compact": 2 * 2 * rows,
@@ -68,7 +74,7 @@ def phase_bytes(wl, name):
 
 # Kernel(s) behind each phase name that caote_evict_timed reports.
 PHASE_KERNELS = {
-    "key_rowstats": r"k_logits_\w+<.*, 0>$", "key_colsum": r"k_logits_\w+<.*, 1>$",
+    "key_rowstats": r"k_logits_\w+<.*, 0>$", "key_colsum": r"k_logits_\w+<.*, [12]>$",
     "merge_stats": r"k_merge_stats", "value_sum": r"k_vsum", "value_final": r"k_vfinal",
     "value_score": r"k_vscore", "select_hist": r"k_select_hist", "select_span": r"k_select_span",
     "select_emit": r"k_select_emit", "compact_gather": r"k_move_rows<0>", "compact_scatter": r"k_move_rows<1>",
@@ -200,7 +206,7 @@ def main():
             acc.setdefault(name, []).append(ms)
     phases = {k: sum(v) / len(v) for k, v in acc.items()}
     dom = max(phases, key=phases.get)
-    dom_bytes = phase_bytes(wl, dom)
+    dom_bytes = phase_bytes(wl, dom, fused_value_sum="key_colsum" in phases and "value_sum" not in phases)
     dom_gbs = dom_bytes / (phases[dom] * 1e-3) / 1e9
     alg = algorithmic_bytes(wl)
     path_gbs = alg["total"] / (ms_per_step * 1e-3) / 1e9
