@@ -64,6 +64,8 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   constexpr int ROWS = WR * RBW * 32;   // query rows per row group
   constexpr bool COLSUM = MODE >= 1;    // sweep 2
   constexpr bool FUSE = MODE == 2;      // sweep 2 that also accumulates sum_j h_j v_j
+  // Q reaches its registers through LDS (where one workgroup per compute unit leaves room)
+  constexpr bool QLDS = NWV == 8;
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
   const int c0 = blockIdx.x * p.split_len;
@@ -77,8 +79,9 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   __shared__ __attribute__((aligned(16))) unsigned char Ks[kNBuf][kTN * kRowBytes];
   __shared__ float a_lds[2][WR][kTN];
   __shared__ int iw_lds[ROWS];          // window position of each row of the group
-  __shared__ float lse_lds[ROWS];       // sweep 2: normaliser of each row of the group
+  __shared__ __attribute__((aligned(16))) float lse_lds[ROWS];   // sweep 2: normaliser of each row of the group
   __shared__ float st_lds[WK][ROWS][2];
+  __shared__ __attribute__((aligned(16))) unsigned char Qs[QLDS ? ROWS * kRowBytes : 16];
   // FUSE: attention mass of the last four tiles, weight of each row of the last four value
   // steps, the H2O accumulator rows of two steps, and one tile of V rows
   __shared__ float af[FUSE ? 4 * kTN : 1];
@@ -110,6 +113,25 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
     // The first two K tiles are requested before anything else, so that their latency
     // overlaps the set-up below.
     __syncthreads();                     // previous row group is done with LDS
+    if (QLDS) {
+      // The Q rows of the group take the same road as the K tiles: whole 256-byte rows by
+      // DMA into LDS (16 lanes per row, swizzled), fragments by ds_read_b128.  Loading the
+      // fragments straight from global memory (32 rows x 32 bytes per instruction) keeps
+      // the address unit busy for several microseconds per workgroup.
+#pragma unroll 1
+      for (int u = 0; u < ROWS * kChunks / kThreads; ++u) {
+        const int slot = (wave * (ROWS * kChunks / kThreads) + u) * kWave + lane;
+        const int row = slot / kChunks, pc = slot % kChunks;
+        if (rg0 + row < p.R) {            // rows past R are not fetched; their fragments are zeroed
+          int g, iw;
+          divmod_w(p, rg0 + row, g, iw);
+          const unsigned char* qp = reinterpret_cast<const unsigned char*>(p.q) +
+              ((int64_t)b * p.qsb + (int64_t)(hk * p.G + g) * p.qsh + (int64_t)iw * p.qsw) * 2;
+          load_to_lds16(qp + ((pc ^ (row & 15)) << 4),
+                        __builtin_amdgcn_readfirstlane(lds_addr(&Qs[(slot - lane) * 16])));
+        }
+      }
+    }
     for (int t = 0; t < kNBuf - 1 && t < ntiles; ++t) issue(t, t);
     // ---- per-row-group set-up: Q fragments, window positions, normalisers ----------
     for (int i = tid; i < ROWS; i += kThreads) {
@@ -119,7 +141,10 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
       if (COLSUM) lse_lds[i] = (rg0 + i) < p.R ? p.lse2[(int64_t)bh * p.Rp + rg0 + i] : INFINITY;
     }
     bf16x8 qf[RBW][8];
-    float lse[RBW][16];
+    // normalisers of the rows a lane meets in sweep 2: in registers, or (fused sweep, which
+    // is short of registers) read from LDS block by block, four consecutive rows per read
+    constexpr bool LSE_REGS = COLSUM && !FUSE;
+    float lse[LSE_REGS ? RBW : 1][16];
     float m_run[RBW], l_run[RBW];
     int nvis_row[RBW];                  // MODE 0: visible-key count of this lane's row
 #pragma unroll
@@ -130,23 +155,40 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
       if (r < p.R) {
         int g, iw;
         divmod_w(p, r, g, iw);
-        const unsigned char* qp = reinterpret_cast<const unsigned char*>(p.q) +
-            ((int64_t)b * p.qsb + (int64_t)(hk * p.G + g) * p.qsh + (int64_t)iw * p.qsw) * 2 + (lane >> 5) * 16;
+        if (!QLDS) {
+          const unsigned char* qp = reinterpret_cast<const unsigned char*>(p.q) +
+              ((int64_t)b * p.qsb + (int64_t)(hk * p.G + g) * p.qsh + (int64_t)iw * p.qsw) * 2 + (lane >> 5) * 16;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-          qf[rb][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + ks * 32));
+          for (int ks = 0; ks < 8; ++ks)
+            qf[rb][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + ks * 32));
+        }
         nvis_row[rb] = p.wic ? P + iw + 1 : N;
       } else {
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qf[rb][ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
       }
     }
-    if (COLSUM) {
-      __syncthreads();
+    if (QLDS) {
+      // the Q rows are older than the K tiles requested after them
+      if (ntiles >= kNBuf - 1) wait_vmcnt<(kNBuf - 1) * LPT>(); else wait_vmcnt<0>();
+    }
+    if (COLSUM || QLDS) __syncthreads();
+    if (LSE_REGS) {
 #pragma unroll
       for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) lse[rb][i] = lse_lds[(wr * RBW + rb) * 32 + m_of(i, lane)];
+    }
+    if (QLDS) {
+#pragma unroll
+      for (int rb = 0; rb < RBW; ++rb) {
+        const int rl = (wr * RBW + rb) * 32 + (lane & 31);
+        if (rg0 + rl < p.R) {
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks)
+            qf[rb][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&Qs[swz(rl, 2 * ks + (lane >> 5))]));
+        }
+      }
     }
     // One 64-key tile out of LDS buffer `buf`.  TAIL: some logits of the tile are masked
     // (keys past the end of the cache, or window keys a row must not see).
@@ -202,9 +244,20 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
           for (int rb = 0; rb < RBW; ++rb) {
             const int rl = (wr * RBW + rb) * 32;                // row offset inside the group
             float e[16];                                        // independent terms, then a tree
+            float nrm[16];
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+              if (LSE_REGS) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) nrm[4 * g4 + i] = lse[LSE_REGS ? rb : 0][4 * g4 + i];
+              } else {
+                const float4 v = *reinterpret_cast<const float4*>(&lse_lds[rl + 8 * g4 + 4 * (lane >> 5)]);
+                nrm[4 * g4] = v.x; nrm[4 * g4 + 1] = v.y; nrm[4 * g4 + 2] = v.z; nrm[4 * g4 + 3] = v.w;
+              }
+            }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-              float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[rb][i], p.c2, -lse[rb][i]));
+              float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[rb][i], p.c2, -nrm[i]));
               if (TAIL) {
                 const int iw = iw_lds[rl + m_of(i, lane)];
                 const bool vis = j < N && iw >= 0 && (!p.wic || j < P + iw + 1);
@@ -318,7 +371,7 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
     for (int rb = 0; rb < RBW; ++rb) {
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qf[rb][ks]));
-      if (COLSUM) {
+      if (LSE_REGS) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) asm volatile("" : : "v"(lse[rb][i]));
       }
