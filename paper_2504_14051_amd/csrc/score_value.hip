@@ -171,23 +171,19 @@ __global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
   const int g = tid / kMaxD, col = tid % kMaxD;
   __shared__ float red[G][kMaxD + 1];
   __shared__ float edge[NW][kMaxD + 1];
+  // The first partial sums are requested here and added up after the boundary tokens below,
+  // whose loads are then in flight at the same time.
   float s = 0.f, z = 0.f;
+  const float* op = p.opart + (int64_t)bh * p.n_vpart * D + (col < D ? col : 0);
+  const float* zp = p.zpart + (int64_t)bh * p.n_vpart;
+  float x0 = 0.f, x1 = 0.f, x2 = 0.f, x3 = 0.f, z0 = 0.f;
   if (col < D) {
-    const float* op = p.opart + (int64_t)bh * p.n_vpart * D + col;
-    int c = g;
-    for (; c + 3 * G < nch; c += 4 * G) {                     // four independent loads in flight
-      const float x0 = op[(int64_t)c * D], x1 = op[(int64_t)(c + G) * D];
-      const float x2 = op[(int64_t)(c + 2 * G) * D], x3 = op[(int64_t)(c + 3 * G) * D];
-      s += x0; s += x1; s += x2; s += x3;
-    }
-    for (; c < nch; c += G) s += op[(int64_t)c * D];
+    if (g < nch) x0 = op[(int64_t)g * D];
+    if (g + G < nch) x1 = op[(int64_t)(g + G) * D];
+    if (g + 2 * G < nch) x2 = op[(int64_t)(g + 2 * G) * D];
+    if (g + 3 * G < nch) x3 = op[(int64_t)(g + 3 * G) * D];
   }
-  if (col == 0) {
-    const float* zp = p.zpart + (int64_t)bh * p.n_vpart;
-    for (int c = g; c < nch; c += G) z += zp[c];
-    red[g][kMaxD] = z;
-  }
-  red[g][col] = s;
+  if (col == 0 && g < nch) z0 = zp[g];
   const bool edges = p.fuse_v && p.halo > 0;    // bf16, head_dim 128: 16 lanes per value row
   if (edges) {
     const int team = tid >> 4, tl = tid & 15, halo = p.halo;
@@ -253,6 +249,16 @@ __global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
       if (lane == 0) edge[wave][kMaxD] = zz;
     }
   }
+  if (col < D) {
+    s += x0; s += x1; s += x2; s += x3;
+    for (int c = g + 4 * G; c < nch; c += G) s += op[(int64_t)c * D];
+  }
+  if (col == 0) {
+    z = z0;
+    for (int c = g + G; c < nch; c += G) z += zp[c];
+    red[g][kMaxD] = z;
+  }
+  red[g][col] = s;
   __syncthreads();
   if (tid <= kMaxD) {
     float t = 0.f;

@@ -22,6 +22,7 @@ constexpr int kT = 256;                   // threads per workgroup
 constexpr int kW = kT / kWave;            // waves per workgroup
 constexpr int kPer = kSelSpan / kT;       // tokens per thread in a span (8)
 constexpr int kRows = kSelSpan / kW / kWave;   // 64-token rows per wave (8)
+constexpr int kSmallCand = 128;           // candidate lists up to this length are ranked in LDS
 static_assert(kPer * kT == kSelSpan && kRows * kW * kWave == kSelSpan, "span geometry");
 
 // Exclusive prefix sum of v over the 256 threads of the block, and the block total.
@@ -189,6 +190,7 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
   __shared__ int pre[kMaxSpans + 1];
   __shared__ uint32_t s_prefix;
   __shared__ int s_krem, s_off, s_ties;
+  __shared__ __attribute__((aligned(16))) uint32_t cl[kSmallCand];   // the head's candidates, if few
 
   uint32_t key[kRows];
   bool valid[kRows];
@@ -232,46 +234,34 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
     return cand[lo * kSelSpan + (i - pre[lo])];
   };
 
-  // ---- finish the radix search on the low 20 bits, over every span's candidates -----------
-  int shift = kHistShift;
-  while (shift > 0) {
-    const int bits = shift >= 8 ? 8 : shift;
-    shift -= bits;
-    const uint32_t himask = 0xffffffffu << (shift + bits);
-    hist[tid] = 0;
+  uint32_t theta;                         // key of the k-th largest score
+  if (ncand <= kSmallCand) {
+    // ---- few candidates: rank them against each other in LDS ------------------------------------
+    // theta is the candidate with fewer than krem candidates above it and at least krem at or
+    // above it; the same pass over the list gives the counts of the earlier spans.
+    for (int i = tid; i < ncand; i += kT) cl[i] = cand_at(i);
+    const int n_pad = ((ncand + 3) & ~3) - ncand;       // zero keys that fill the last uint4
+    if (tid < n_pad) cl[ncand + tid] = 0u;
+    if (tid == 0) { s_prefix = prefix; s_krem = 0; }    // (no candidate: not reached, krem >= 1)
     __syncthreads();
     for (int i = tid; i < ncand; i += kT) {
-      const uint32_t ck = cand_at(i);
-      if ((ck & himask) == prefix) atomicAdd(&hist[(ck >> shift) & ((1u << bits) - 1u)], 1);
-    }
-    __syncthreads();
-    {                                     // walk down from the largest digit, in parallel
-      const int nd = 1 << bits;
-      const int mine = tid < nd ? hist[nd - 1 - tid] : 0;
-      int total;
-      const int above = block_excl_scan(mine, wave_tot, total);
-      if (tid < nd && above < krem && krem <= above + mine) {   // exactly one thread
-        s_prefix = prefix | ((uint32_t)(nd - 1 - tid) << shift);
-        s_krem = krem - above;
+      const uint32_t mine = cl[i];
+      int gt = 0, ge = 0;
+      for (int c = 0; c < ncand; c += 4) {
+        const uint4 v = *reinterpret_cast<const uint4*>(&cl[c]);
+        gt += (v.x > mine) + (v.y > mine) + (v.z > mine) + (v.w > mine);
+        ge += (v.x >= mine) + (v.y >= mine) + (v.z >= mine) + (v.w >= mine);
       }
+      if (mine == 0u) ge -= n_pad;        // the padding is no candidate
+      if (gt < krem && krem <= ge) { s_prefix = mine; s_krem = krem - gt; }   // ties write the same
     }
     __syncthreads();
-    prefix = s_prefix;
+    theta = s_prefix;
     krem = s_krem;
-    __syncthreads();
-  }
-  // prefix = key of the k-th largest score; krem = how many of its ties are kept.
-  const uint32_t theta = prefix;
-
-  // ---- where this span's survivors start ---------------------------------------------------------
-  // The earlier spans keep their keys in higher bins, their candidates above theta, and, since
-  // ties go to the lowest indices, the first min(krem, ties before this span) ties.
-  {
     int gt = 0, eq = 0;
     for (int i = tid; i < pre[me]; i += kT) {
-      const uint32_t ck = cand_at(i);
-      gt += ck > theta;
-      eq += ck == theta;
+      gt += cl[i] > theta;
+      eq += cl[i] == theta;
     }
     int total_gt, total_eq;
     block_excl_scan(gt, wave_tot, total_gt);
@@ -281,6 +271,57 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
       s_ties = max(0, krem - total_eq);
     }
     __syncthreads();
+  } else {
+    // ---- finish the radix search on the low 20 bits, over every span's candidates -----------
+    int shift = kHistShift;
+    while (shift > 0) {
+      const int bits = shift >= 8 ? 8 : shift;
+      shift -= bits;
+      const uint32_t himask = 0xffffffffu << (shift + bits);
+      hist[tid] = 0;
+      __syncthreads();
+      for (int i = tid; i < ncand; i += kT) {
+        const uint32_t ck = cand_at(i);
+        if ((ck & himask) == prefix) atomicAdd(&hist[(ck >> shift) & ((1u << bits) - 1u)], 1);
+      }
+      __syncthreads();
+      {                                     // walk down from the largest digit, in parallel
+        const int nd = 1 << bits;
+        const int mine = tid < nd ? hist[nd - 1 - tid] : 0;
+        int total;
+        const int above = block_excl_scan(mine, wave_tot, total);
+        if (tid < nd && above < krem && krem <= above + mine) {   // exactly one thread
+          s_prefix = prefix | ((uint32_t)(nd - 1 - tid) << shift);
+          s_krem = krem - above;
+        }
+      }
+      __syncthreads();
+      prefix = s_prefix;
+      krem = s_krem;
+      __syncthreads();
+    }
+    // prefix = key of the k-th largest score; krem = how many of its ties are kept.
+    theta = prefix;
+
+    // ---- where this span's survivors start ---------------------------------------------------------
+    // The earlier spans keep their keys in higher bins, their candidates above theta, and, since
+    // ties go to the lowest indices, the first min(krem, ties before this span) ties.
+    {
+      int gt = 0, eq = 0;
+      for (int i = tid; i < pre[me]; i += kT) {
+        const uint32_t ck = cand_at(i);
+        gt += ck > theta;
+        eq += ck == theta;
+      }
+      int total_gt, total_eq;
+      block_excl_scan(gt, wave_tot, total_gt);
+      block_excl_scan(eq, wave_tot, total_eq);
+      if (tid == 0) {
+        s_off = hi_before + total_gt + min(krem, total_eq);
+        s_ties = max(0, krem - total_eq);
+      }
+      __syncthreads();
+    }
   }
   const int span_off = s_off;             // output position of this span's first survivor
   const int span_ties = s_ties;           // ties this span may still keep
