@@ -95,6 +95,7 @@ __global__ __launch_bounds__(kThreads) void k_rowstats_small(const Params p) {
       const int j = min(j0 + u * KPI, c1 - 1);            // clamped: stays inside the chunk
       kfetch(Kb + (int64_t)j * p.ksn, f[u]);
     }
+    float t[kKeysInFlight];               // this lane's row against the keys of the step
 #pragma unroll
     for (int u = 0; u < kKeysInFlight; ++u) {
       const int j = j0 + u * KPI;
@@ -109,17 +110,21 @@ __global__ __launch_bounds__(kThreads) void k_rowstats_small(const Params p) {
         s = team_sum_dpp<TL>(s);
         mine = rr == myr ? s : mine;
       }
-      if (j < c1) {                                        // uniform within the team
-        float t = mine * p.c2;
-        const bool vis = j < nvis_my && myr < p.R;
-        t = vis ? t : -INFINITY;
-        if (tl < RT) Sb[(int64_t)j * RT + tl] = t;         // lane tl holds row tl
-        if (vis) {
-          const float mn = fmaxf(m, t);
-          l = l * exp2f(m - mn) + exp2f(t - mn);
-          m = mn;
-        }
-      }
+      const bool vis = j < c1 && j < nvis_my && myr < p.R;
+      t[u] = vis ? mine * p.c2 : -INFINITY;
+      if (j < c1 && tl < RT) Sb[(int64_t)j * RT + tl] = t[u];   // lane tl holds row tl
+    }
+    // one rescale of the running sum per step, not per key
+    float mx = t[0];
+#pragma unroll
+    for (int u = 1; u < kKeysInFlight; ++u) mx = fmaxf(mx, t[u]);
+    const float mn = fmaxf(m, mx);
+    if (mn > -INFINITY) {
+      float s = 0.f;
+#pragma unroll
+      for (int u = 0; u < kKeysInFlight; ++u) s += __builtin_amdgcn_exp2f(t[u] - mn);   // exp2(-inf) = 0
+      l = l * __builtin_amdgcn_exp2f(m - mn) + s;
+      m = mn;
     }
   }
   if (tl < RT) { red[team][tl][0] = m; red[team][tl][1] = l; }

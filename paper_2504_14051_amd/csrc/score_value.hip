@@ -53,11 +53,11 @@ __device__ __forceinline__ float mass_of(const Params& p, int bh, int j, const f
   float a = 0.f;
   if (p.s_rows == 4) {
     const float4 v = *reinterpret_cast<const float4*>(t);
-    a = (exp2f(v.x - lse[0]) + exp2f(v.y - lse[1])) + (exp2f(v.z - lse[2]) + exp2f(v.w - lse[3]));
+    a = (__builtin_amdgcn_exp2f(v.x - lse[0]) + __builtin_amdgcn_exp2f(v.y - lse[1])) + (__builtin_amdgcn_exp2f(v.z - lse[2]) + __builtin_amdgcn_exp2f(v.w - lse[3]));
   } else {
     const float4 v = *reinterpret_cast<const float4*>(t), w = *reinterpret_cast<const float4*>(t + 4);
-    a = ((exp2f(v.x - lse[0]) + exp2f(v.y - lse[1])) + (exp2f(v.z - lse[2]) + exp2f(v.w - lse[3]))) +
-        ((exp2f(w.x - lse[4]) + exp2f(w.y - lse[5])) + (exp2f(w.z - lse[6]) + exp2f(w.w - lse[7])));
+    a = ((__builtin_amdgcn_exp2f(v.x - lse[0]) + __builtin_amdgcn_exp2f(v.y - lse[1])) + (__builtin_amdgcn_exp2f(v.z - lse[2]) + __builtin_amdgcn_exp2f(v.w - lse[3]))) +
+        ((__builtin_amdgcn_exp2f(w.x - lse[4]) + __builtin_amdgcn_exp2f(w.y - lse[5])) + (__builtin_amdgcn_exp2f(w.z - lse[6]) + __builtin_amdgcn_exp2f(w.w - lse[7])));
   }
   return a;
 }
