@@ -56,6 +56,13 @@ def lib():
         L.oracle_caote_scores.argtypes = [_dp, _dp, i, i, i, i, i, _dp, _dp, _dp]
         L.oracle_caote_scores.restype = None
         L.oracle_score.argtypes = [_dp, _dp, _dp, _dp, i, i, i, i, dbl, i, i, i, i, i, i, _dp, _dp]
+        L.oracle_score_given_lse.restype = ctypes.c_int
+        L.oracle_score_given_lse.argtypes = [_dp, _dp, _dp, _dp, i, i, i, i, dbl, i, i, i, i, i, i,
+                                             _dp, _dp, _dp]
+        L.oracle_window_attention_given_lse.restype = ctypes.c_int
+        L.oracle_window_attention_given_lse.argtypes = [_dp, _dp, i, i, i, i, dbl, i, _dp, _dp]
+        L.oracle_row_lse.restype = ctypes.c_int
+        L.oracle_row_lse.argtypes = [_dp, _dp, i, i, i, i, dbl, i, _dp]
         L.oracle_score.restype = i
         L.oracle_select.argtypes = [_dp, i, i, _ip]
         L.oracle_select.restype = None
@@ -90,6 +97,33 @@ def window_attention(q, k, G, W, scale, window_in_cache):
                                        A.ctypes.data_as(_dp))
     if rc != 0:
         raise ValueError("oracle_window_attention: a query row has no visible key")
+    return A
+
+
+def row_lse(q, k, G, W, scale, window_in_cache):
+    """q [G*W, d], k [N, d] -> natural-log normaliser of every query row, [G*W]."""
+    q, qp = _d(q)
+    k, kp = _d(k)
+    N, d = k.shape
+    out = np.empty(G * W, dtype=np.float64)
+    rc = lib().oracle_row_lse(qp, kp, G, W, N, d, float(scale), int(window_in_cache),
+                              out.ctypes.data_as(_dp))
+    if rc != 0:
+        raise ValueError("oracle_row_lse: a query row has no visible key")
+    return out
+
+
+def window_attention_given_lse(q, k, G, W, scale, window_in_cache, lse):
+    """A_rj = exp(scale q_r.k_j - lse_r) for the visible keys, 0 elsewhere."""
+    q, qp = _d(q)
+    k, kp = _d(k)
+    lse, lp = _d(lse)
+    N, d = k.shape
+    A = np.empty((G * W, N), dtype=np.float64)
+    rc = lib().oracle_window_attention_given_lse(qp, kp, G, W, N, d, float(scale),
+                                                 int(window_in_cache), lp, A.ctypes.data_as(_dp))
+    if rc != 0:
+        raise ValueError("oracle_window_attention_given_lse: a query row has no visible key")
     return A
 
 
@@ -128,8 +162,9 @@ def caote_scores(h, v, lo=0, hi=None, fast=False):
 
 
 def score_one(q, k, v, h_in, G, W, scale, window_in_cache, base, pool_kernel=1,
-              n_protect_head=0, n_protect_tail=0, fast=False):
-    """One (sequence, KV head).  Returns (c [N], h [N], a [N])."""
+              n_protect_head=0, n_protect_tail=0, fast=False, lse=None):
+    """One (sequence, KV head).  Returns (c [N], h [N], a [N]).  lse: the caller's row
+    normalisers [G*W] (natural log) or None."""
     q, qp = _d(q)
     k, kp = _d(k)
     v, vp = _d(v)
@@ -137,10 +172,15 @@ def score_one(q, k, v, h_in, G, W, scale, window_in_cache, base, pool_kernel=1,
     h = np.zeros(N, dtype=np.float64) if h_in is None else np.array(h_in, dtype=np.float64)
     c = np.empty(N, dtype=np.float64)
     a = np.empty(N, dtype=np.float64)
-    rc = lib().oracle_score(qp, kp, vp, h.ctypes.data_as(_dp), G, W, N, d, float(scale),
-                            int(window_in_cache), base, pool_kernel, n_protect_head,
-                            n_protect_tail, int(fast), c.ctypes.data_as(_dp),
-                            a.ctypes.data_as(_dp))
+    if lse is not None:
+        lse, lp = _d(lse)
+        assert lse.shape == (G * W,)
+    else:
+        lp = None
+    rc = lib().oracle_score_given_lse(qp, kp, vp, h.ctypes.data_as(_dp), G, W, N, d,
+                                      float(scale), int(window_in_cache), base, pool_kernel,
+                                      n_protect_head, n_protect_tail, int(fast), lp,
+                                      c.ctypes.data_as(_dp), a.ctypes.data_as(_dp))
     if rc != 0:
         raise ValueError(f"oracle_score failed rc={rc}")
     return c, h, a
@@ -198,11 +238,12 @@ def joint_eviction_error(w, v, token_set):
 
 def score_batched(q, K, V, h_in, seq_lens, *, n_kv_heads, window, scale, window_in_cache,
                   base, pool_kernel=1, n_protect_head=0, n_protect_tail=0, fast=False,
-                  threads=1):
+                  threads=1, lse=None):
     """q [B, Hq, W, d], K/V [B, Hkv, cap, d], h_in [B, Hkv, cap] or None,
     seq_lens [B] or None.  Returns (scores, h, a), each [B, Hkv, cap] fp64; entries at
     or beyond a sequence's length are NaN.  The ctypes calls release the GIL, so
-    `threads` > 1 runs instances on several cores."""
+    `threads` > 1 runs instances on several cores.  lse: [B, Hq, W] row normalisers handed
+    over by the caller (natural log) or None."""
     q = np.asarray(q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
@@ -221,8 +262,9 @@ def score_batched(q, K, V, h_in, seq_lens, *, n_kv_heads, window, scale, window_
             return
         qg = q[b, hk * G:(hk + 1) * G].reshape(G * W, d)
         hin = None if h_in is None else np.asarray(h_in[b, hk, :N], dtype=np.float64)
+        lg = None if lse is None else np.asarray(lse[b, hk * G:(hk + 1) * G], dtype=np.float64).reshape(G * W)
         c, h, a = score_one(qg, K[b, hk, :N], V[b, hk, :N], hin, G, W, scale, window_in_cache,
-                            base, pool_kernel, n_protect_head, n_protect_tail, fast)
+                            base, pool_kernel, n_protect_head, n_protect_tail, fast, lg)
         out_c[b, hk, :N], out_h[b, hk, :N], out_a[b, hk, :N] = c, h, a
 
     work = [(b, hk) for b in range(B) for hk in range(n_kv_heads)]

@@ -72,6 +72,69 @@ int oracle_window_attention(const double *q, const double *k, int G, int W,
     return 0;
 }
 
+/* ------------------------------------------------------------------------- *
+ * The same attention slice when the caller hands over the softmax normalisers
+ * of its own attention pass (App. C counts only the value-side work of the score:
+ * the attention weights are taken to exist already).  row_lse[r] is the natural
+ * logarithm of sum_j exp(scale * q_r.k_j) over the keys visible to row r, so
+ *   A_rj = exp(scale * q_r.k_j - row_lse[r]).
+ * Nothing is renormalised here: with an exact row_lse the rows sum to 1, with a
+ * shifted one they do not, and that is the caller's statement, not ours.
+ *   q [G*W][d], k [N][d], row_lse [G*W]  ->  A [G*W][N]
+ * ------------------------------------------------------------------------- */
+int oracle_window_attention_given_lse(const double *q, const double *k, int G, int W,
+                                      int N, int d, double scale, int window_in_cache,
+                                      const double *row_lse, double *A)
+{
+    int R = G * W;
+    int P = window_in_cache ? N - W : N;
+    if (window_in_cache && N < W) return -1;
+    if (N < 1) return -1;
+    for (int r = 0; r < R; ++r) {
+        int i = r % W;
+        int n_vis = window_in_cache ? P + i + 1 : N;
+        if (n_vis < 1) return -1;
+        double *Ar = A + (size_t)r * N;
+        for (int j = 0; j < n_vis; ++j) {
+            double s = 0.0;
+            for (int c = 0; c < d; ++c) s += q[(size_t)r * d + c] * k[(size_t)j * d + c];
+            Ar[j] = exp(s * scale - row_lse[r]);
+        }
+        for (int j = n_vis; j < N; ++j) Ar[j] = 0.0;
+    }
+    return 0;
+}
+
+/* What such a caller would hand over: row_lse[r] = log sum_j exp(scale * q_r.k_j)
+ * over the visible keys, by the definition (maximum taken out for range only).   */
+int oracle_row_lse(const double *q, const double *k, int G, int W, int N, int d,
+                   double scale, int window_in_cache, double *row_lse)
+{
+    int R = G * W;
+    int P = window_in_cache ? N - W : N;
+    if (window_in_cache && N < W) return -1;
+    if (N < 1) return -1;
+    double *s = (double *)malloc((size_t)N * sizeof(double));
+    if (!s) return -2;
+    for (int r = 0; r < R; ++r) {
+        int i = r % W;
+        int n_vis = window_in_cache ? P + i + 1 : N;
+        if (n_vis < 1) { free(s); return -1; }
+        double mx = -INFINITY;
+        for (int j = 0; j < n_vis; ++j) {
+            double t = 0.0;
+            for (int c = 0; c < d; ++c) t += q[(size_t)r * d + c] * k[(size_t)j * d + c];
+            s[j] = t * scale;
+            if (s[j] > mx) mx = s[j];
+        }
+        double den = 0.0;
+        for (int j = 0; j < n_vis; ++j) den += exp(s[j] - mx);
+        row_lse[r] = mx + log(den);
+    }
+    free(s);
+    return 0;
+}
+
 /* Column sums of the attention slice: the H2O score function of Sec. 2,
  * f_score,j = sum_i A_{i,j}, summed here over every query row of the group
  * (all G heads, all W positions).   A [R][N] -> a [N]                        */
@@ -166,11 +229,30 @@ void oracle_caote_scores(const double *h, const double *v, int N, int d, int lo,
  * (for the other bases it only receives h; may be NULL).  a_out optional.
  * Returns 0, -1 on a row with no visible key, -2 on allocation failure.
  * ------------------------------------------------------------------------- */
+int oracle_score_given_lse(const double *q, const double *k, const double *v,
+                           double *h_inout, int G, int W, int N, int d, double scale,
+                           int window_in_cache, int base, int pool_kernel,
+                           int n_protect_head, int n_protect_tail, int fast,
+                           const double *row_lse, double *c, double *a_out);
+
 int oracle_score(const double *q, const double *k, const double *v,
                  double *h_inout, int G, int W, int N, int d, double scale,
                  int window_in_cache, int base, int pool_kernel,
                  int n_protect_head, int n_protect_tail, int fast, double *c,
                  double *a_out)
+{
+    return oracle_score_given_lse(q, k, v, h_inout, G, W, N, d, scale, window_in_cache, base,
+                                  pool_kernel, n_protect_head, n_protect_tail, fast, NULL, c,
+                                  a_out);
+}
+
+/* The same with the caller's row normalisers (row_lse != NULL), see
+ * oracle_window_attention_given_lse; row_lse == NULL is oracle_score.               */
+int oracle_score_given_lse(const double *q, const double *k, const double *v,
+                           double *h_inout, int G, int W, int N, int d, double scale,
+                           int window_in_cache, int base, int pool_kernel,
+                           int n_protect_head, int n_protect_tail, int fast,
+                           const double *row_lse, double *c, double *a_out)
 {
     int R = G * W;
     int lo = n_protect_head, hi = N - n_protect_tail;
@@ -180,7 +262,9 @@ int oracle_score(const double *q, const double *k, const double *v,
     double *a = (double *)malloc((size_t)N * sizeof(double));
     double *h = (double *)malloc((size_t)N * sizeof(double));
     if (!A || !a || !h) { free(A); free(a); free(h); return -2; }
-    int rc = oracle_window_attention(q, k, G, W, N, d, scale, window_in_cache, A);
+    int rc = row_lse ? oracle_window_attention_given_lse(q, k, G, W, N, d, scale,
+                                                         window_in_cache, row_lse, A)
+                     : oracle_window_attention(q, k, G, W, N, d, scale, window_in_cache, A);
     if (rc == 0) {
         oracle_column_sums(A, R, N, a);
         oracle_base_score(a, base == ORACLE_BASE_H2O ? h_inout : NULL, N, base,

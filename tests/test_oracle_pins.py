@@ -375,3 +375,67 @@ def test_batched_wrapper_matches_single_instances(oracle):
     assert np.isnan(c[b, hk, N:]).all()
     kept = oracle.select_batched(c, lens, 40)
     np.testing.assert_array_equal(kept[b, hk], oracle.select_one(c1, 40))
+
+
+# ---- row normalisers handed over by the caller (App. C: the attention weights exist already) --
+
+def _masked_logits(q, k, W, scale, wic):
+    R, N = q.shape[0], k.shape[0]
+    s = (q @ k.T) * scale
+    if wic:
+        i = np.arange(R) % W
+        vis = np.arange(N)[None, :] < (N - W + i + 1)[:, None]
+        s = np.where(vis, s, -np.inf)
+    return s
+
+
+@pytest.mark.parametrize("G,W,N,d,wic", [(1, 1, 9, 4, 0), (2, 3, 17, 8, 1), (4, 8, 40, 16, 1), (7, 2, 33, 8, 0)])
+def test_row_lse_is_the_library_logsumexp(oracle, G, W, N, d, wic):
+    q = RNG.standard_normal((G * W, d))
+    k = RNG.standard_normal((N, d)) * 2.0
+    scale = 0.7 / np.sqrt(d)
+    s = _masked_logits(q, k, W, scale, wic)
+    np.testing.assert_allclose(oracle.row_lse(q, k, G, W, scale, wic),
+                               scipy.special.logsumexp(s, axis=1), rtol=1e-13)
+
+
+@pytest.mark.parametrize("G,W,N,d,wic", [(2, 3, 17, 8, 1), (4, 4, 64, 16, 1), (1, 5, 21, 8, 0)])
+def test_given_lse_reproduces_the_softmax_and_the_scores(oracle, G, W, N, d, wic):
+    q = RNG.standard_normal((G * W, d))
+    k = RNG.standard_normal((N, d))
+    v = RNG.standard_normal((N, d))
+    scale = 1.0 / np.sqrt(d)
+    s = _masked_logits(q, k, W, scale, wic)
+    lse = scipy.special.logsumexp(s, axis=1)                    # the caller's normalisers
+    A = oracle.window_attention_given_lse(q, k, G, W, scale, wic, lse)
+    np.testing.assert_allclose(A, scipy.special.softmax(s, axis=1), rtol=1e-12, atol=1e-300)
+    for base, h_in in ((oracle.BASE_NONE, None), (oracle.BASE_H2O, RNG.random(N)),
+                       (oracle.BASE_SNAPKV, None)):
+        kw = dict(pool_kernel=3, n_protect_tail=W if base == oracle.BASE_SNAPKV else 0)
+        c0, h0, a0 = oracle.score_one(q, k, v, h_in, G, W, scale, wic, base, **kw)
+        c1, h1, a1 = oracle.score_one(q, k, v, h_in, G, W, scale, wic, base, lse=lse, **kw)
+        np.testing.assert_allclose(a1, a0, rtol=1e-12)
+        np.testing.assert_allclose(h1, h0, rtol=1e-12)
+        np.testing.assert_allclose(c1, c0, rtol=1e-9, atol=1e-14)
+
+
+def test_shifted_lse_scales_the_attention_mass(oracle):
+    """lse + log 2 halves every column sum: nothing is renormalised behind the caller's back.
+    Without an accumulator the scores do not change (w = h / sum h); with one they follow
+    h = h_in + a / 2."""
+    G, W, N, d = 2, 4, 30, 8
+    q = RNG.standard_normal((G * W, d))
+    k = RNG.standard_normal((N, d))
+    v = RNG.standard_normal((N, d))
+    scale = 1.0 / np.sqrt(d)
+    lse = oracle.row_lse(q, k, G, W, scale, 1)
+    c0, h0, a0 = oracle.score_one(q, k, v, None, G, W, scale, 1, oracle.BASE_NONE, lse=lse)
+    c1, h1, a1 = oracle.score_one(q, k, v, None, G, W, scale, 1, oracle.BASE_NONE, lse=lse + np.log(2.0))
+    np.testing.assert_allclose(a1, a0 / 2, rtol=1e-13)
+    np.testing.assert_allclose(c1, c0, rtol=1e-10)
+    assert np.isclose(a0.sum(), G * W, rtol=1e-12) and np.isclose(a1.sum(), G * W / 2, rtol=1e-12)
+    h_in = RNG.random(N)
+    c2, h2, a2 = oracle.score_one(q, k, v, h_in, G, W, scale, 1, oracle.BASE_H2O, lse=lse + np.log(2.0))
+    np.testing.assert_allclose(h2, h_in + a0 / 2, rtol=1e-13)
+    c3, _, _ = oracle.caote_scores(h_in + a0 / 2, v)
+    np.testing.assert_allclose(c2, c3, rtol=1e-12)
