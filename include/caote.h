@@ -94,6 +94,16 @@ typedef struct caote_layout {
   int32_t n_protect_head;    /* first rows are never evicted                          */
   int32_t n_protect_tail;    /* last rows are never evicted (SnapKV: the window)      */
   int32_t variant;           /* caote_variant                                         */
+  const float* row_lse;      /* DEVICE [batch][n_q_heads][window] fp32, dense, or NULL.
+                                Softmax normalisers handed over by the caller's own
+                                attention pass (App. C prices the score as value-side
+                                work only: the attention weights exist already):
+                                row_lse = ln sum_j exp(softmax_scale * q.k_j) over the
+                                keys visible to that query row (the "LSE" an attention
+                                kernel keeps for its backward pass).  When given, the
+                                first sweep over K is skipped and A_rj =
+                                exp(softmax_scale * q_r.k_j - row_lse_r); nothing is
+                                renormalised.  Must be finite.  NULL: computed here.  */
 } caote_layout;
 
 /* Bytes of workspace that any entry point may need for this layout and budget.

@@ -46,6 +46,7 @@ class Layout(ctypes.Structure):
         ("pool_kernel", ctypes.c_int32), ("window_in_cache", ctypes.c_int32),
         ("n_protect_head", ctypes.c_int32), ("n_protect_tail", ctypes.c_int32),
         ("variant", ctypes.c_int32),
+        ("row_lse", ctypes.c_void_p),
     ]
 
 
@@ -107,12 +108,16 @@ def _stream(stream) -> int | None:
 
 
 def make_layout(q, K, V, *, base, softmax_scale, window_in_cache=1, pool_kernel=1,
-                n_protect_head=0, n_protect_tail=0, variant=EXACT, seq_lens=None) -> Layout:
-    """Layout of q [B,Hq,W,d], K/V [B,Hkv,cap,d] (innermost dimension contiguous)."""
+                n_protect_head=0, n_protect_tail=0, variant=EXACT, seq_lens=None,
+                row_lse=None) -> Layout:
+    """Layout of q [B,Hq,W,d], K/V [B,Hkv,cap,d] (innermost dimension contiguous).
+    row_lse: optional fp32 device tensor [B,Hq,W], the caller's softmax normalisers."""
     B, Hq, W, d = q.shape
     _, Hkv, cap, _ = K.shape
     assert q.stride(3) == 1 and K.stride(3) == 1 and V.stride(3) == 1
     assert q.dtype == K.dtype == V.dtype and q.dtype in (torch.bfloat16, torch.float32)
+    if row_lse is not None:
+        assert row_lse.dtype == torch.float32 and row_lse.is_contiguous() and tuple(row_lse.shape) == (B, Hq, W)
     return Layout(
         batch=B, n_q_heads=Hq, n_kv_heads=Hkv, head_dim=d, window=W, capacity=cap,
         seq_lens=_ptr(seq_lens),
@@ -121,7 +126,8 @@ def make_layout(q, K, V, *, base, softmax_scale, window_in_cache=1, pool_kernel=
         q_stride_b=q.stride(0), q_stride_h=q.stride(1), q_stride_w=q.stride(2),
         dtype=BF16 if q.dtype == torch.bfloat16 else F32, base=base,
         softmax_scale=softmax_scale, pool_kernel=pool_kernel, window_in_cache=window_in_cache,
-        n_protect_head=n_protect_head, n_protect_tail=n_protect_tail, variant=variant)
+        n_protect_head=n_protect_head, n_protect_tail=n_protect_tail, variant=variant,
+        row_lse=_ptr(row_lse))
 
 
 def caote_version() -> int:
@@ -183,9 +189,10 @@ def caote_evict_timed(q_window, K, V, base_score, layout: Layout, budget: int, m
     return [(lib().caote_phase_name(i).decode(), float(ms[i])) for i in range(n.value)]
 
 
-def layout_for(wl, cache_dev) -> Layout:
+def layout_for(wl, cache_dev, row_lse=None) -> Layout:
     """Layout of a `synth.Cache` whose tensors live on the device, for workload `wl`."""
     return make_layout(cache_dev.q, cache_dev.K, cache_dev.V, base=wl.base,
                        softmax_scale=wl.softmax_scale, window_in_cache=wl.window_in_cache,
                        pool_kernel=wl.pool_kernel, n_protect_head=wl.n_protect_head,
-                       n_protect_tail=wl.n_protect_tail, seq_lens=cache_dev.seq_lens)
+                       n_protect_tail=wl.n_protect_tail, seq_lens=cache_dev.seq_lens,
+                       row_lse=row_lse)

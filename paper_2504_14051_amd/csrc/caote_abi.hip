@@ -57,6 +57,8 @@ caote_status check_layout(const caote_layout* L, int32_t budget, bool need_budge
   }
   if (L->k_stride_n < L->head_dim || L->v_stride_n < L->head_dim || L->q_stride_w < L->head_dim)
     return fail(CAOTE_EINVAL, "row stride smaller than head_dim");
+  if (L->row_lse && ((uintptr_t)L->row_lse % sizeof(float)) != 0)
+    return fail(CAOTE_EINVAL, "row_lse is not aligned to 4 bytes");
   if ((int64_t)L->batch * L->n_kv_heads > 65535)
     return fail(CAOTE_EUNSUPPORTED, "batch * n_kv_heads > 65535");
   if (need_budget && budget < 1) return fail(CAOTE_EINVAL, "budget must be >= 1");
@@ -70,6 +72,7 @@ caote_status check_layout(const caote_layout* L, int32_t budget, bool need_budge
 size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   memset(&p, 0, sizeof(p));
   p.seq_lens = L->seq_lens;
+  p.lse_in = L->row_lse;
   p.B = L->batch; p.Hq = L->n_q_heads; p.Hkv = L->n_kv_heads; p.G = p.Hq / p.Hkv;
   p.D = L->head_dim; p.W = L->window; p.R = p.G * p.W; p.cap = L->capacity;
   p.ksb = L->k_stride_b; p.ksh = L->k_stride_h; p.ksn = L->k_stride_n;
@@ -178,7 +181,7 @@ extern "C" {
 
 const char* caote_last_error(void) { return g_err; }
 
-int32_t caote_version(void) { return 100; }
+int32_t caote_version(void) { return 101; }
 
 size_t caote_workspace_bytes(const caote_layout* layout, int32_t budget) {
   if (check_layout(layout, budget, false) != CAOTE_OK) return 0;
@@ -248,7 +251,9 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
   if (st != CAOTE_OK) return st;
   p.q = q_window; p.K = K; p.V = V; p.base = base_score; p.scores = scores; p.kept = kept_idx;
   p.mode = mode;
-  p.hist_zeroed = 1;
+  // the merge of the row statistics (or, on the matrix-core path, the second sweep) clears
+  // the selection's counters on its way
+  p.hist_zeroed = (!p.lse_in || p.use_mfma) ? 1 : 0;
   if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
   st = do_score(p, s, hook);
   if (st != CAOTE_OK) return st;

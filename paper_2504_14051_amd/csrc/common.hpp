@@ -24,6 +24,7 @@ struct Params {
   float* base;        // H2O accumulator (in/out) or nullptr
   float* scores;      // out
   const int32_t* seq_lens;
+  const float* lse_in;// [B][Hq][W] natural-log row normalisers from the caller, or nullptr
   int32_t* kept;      // [BH][budget]
   int B, Hq, Hkv, G, D, W, R, cap;
   int64_t ksb, ksh, ksn, vsb, vsh, vsn, qsb, qsh, qsw;
@@ -95,6 +96,17 @@ __device__ __forceinline__ void divmod_w(const Params& p, int r, int& q, int& m)
   m = r - q * p.W;
   if (m < 0) { m += p.W; --q; }
   else if (m >= p.W) { m -= p.W; ++q; }
+}
+
+// log2-domain normaliser of query row r of head bh = (b, hk): the caller's, or the one the
+// first key sweep left in the workspace.
+__device__ __forceinline__ float row_lse2(const Params& p, int b, int hk, int bh, int r) {
+  if (p.lse_in) {
+    int g, iw;
+    divmod_w(p, r, g, iw);
+    return p.lse_in[((int64_t)b * p.Hq + hk * p.G + g) * p.W + iw] * 1.4426950408889634f;
+  }
+  return p.lse2[(int64_t)bh * p.Rp + r];
 }
 
 // Clears the per-head counters that later kernels of the same call accumulate into.

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kThreads) void k_logits_generic(const Params p) {
         const int g = r / p.W, i = r % p.W;
         load8(Qb + (int64_t)(hk * p.G + g) * p.qsh + (int64_t)i * p.qsw, qf[rr]);
         nvis[rr] = p.wic ? P + i + 1 : N;
-        if (MODE == 1) lse[rr] = p.lse2[(int64_t)bh * p.Rp + r];
+        if (MODE == 1) lse[rr] = row_lse2(p, b, hk, bh, r);
       }
     }
     for (int j = c0 + team; j < c1; j += KPI) {
@@ -129,10 +129,12 @@ __global__ void k_merge_stats(const Params p) {
 template <typename T, int D>
 hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_split, p.B * p.Hkv);
-  hipLaunchKernelGGL((k_logits_generic<T, D, 0>), grid, dim3(kThreads), 0, s, p);
-  mark(hook, "key_rowstats");
-  hipLaunchKernelGGL(k_merge_stats, dim3((p.R + 63) / 64, p.B * p.Hkv), dim3(64), 0, s, p);
-  mark(hook, "merge_stats");
+  if (!p.lse_in) {                       // else the caller's attention pass has done sweep 1
+    hipLaunchKernelGGL((k_logits_generic<T, D, 0>), grid, dim3(kThreads), 0, s, p);
+    mark(hook, "key_rowstats");
+    hipLaunchKernelGGL(k_merge_stats, dim3((p.R + 63) / 64, p.B * p.Hkv), dim3(64), 0, s, p);
+    mark(hook, "merge_stats");
+  }
   hipLaunchKernelGGL((k_logits_generic<T, D, 1>), grid, dim3(kThreads),
                      (size_t)p.split_len * sizeof(float), s, p);
   mark(hook, "key_colsum");

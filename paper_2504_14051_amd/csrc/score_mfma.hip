@@ -69,6 +69,9 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
   const int c0 = blockIdx.x * p.split_len;
+  // with the caller's normalisers this is the first kernel of the call: it clears the
+  // selection's counters (otherwise the merge of the row statistics does)
+  if (COLSUM && p.lse_in && blockIdx.x == 0) reset_counters(p, bh);
   if (c0 >= N) return;
   const int c1 = min(N, c0 + p.split_len);
   const int ntiles = (c1 - c0 + kTN - 1) / kTN;
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
       int g_unused, iw_i;
       divmod_w(p, rg0 + i, g_unused, iw_i);
       iw_lds[i] = (rg0 + i) < p.R ? iw_i : -1;
-      if (COLSUM) lse_lds[i] = (rg0 + i) < p.R ? p.lse2[(int64_t)bh * p.Rp + rg0 + i] : INFINITY;
+      if (COLSUM) lse_lds[i] = (rg0 + i) < p.R ? row_lse2(p, b, hk, bh, rg0 + i) : INFINITY;
     }
     bf16x8 qf[RBW][8];
     // normalisers of the rows a lane meets in sweep 2: in registers, or (fused sweep, which
@@ -497,9 +500,11 @@ namespace {
 template <int NWV, int WR, int RBW>
 hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_split, p.B * p.Hkv);
-  hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid, dim3(NWV * kWave), 0, s, p);
-  mark(hook, "key_rowstats");
-  if (launch_merge_stats(p, s, hook) != hipSuccess) return hipGetLastError();
+  if (!p.lse_in) {                       // else the caller's attention pass has done sweep 1
+    hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid, dim3(NWV * kWave), 0, s, p);
+    mark(hook, "key_rowstats");
+    if (launch_merge_stats(p, s, hook) != hipSuccess) return hipGetLastError();
+  }
   if (p.fuse_v) hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 2>), grid, dim3(NWV * kWave), 0, s, p);
   else          hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 1>), grid, dim3(NWV * kWave), 0, s, p);
   mark(hook, "key_colsum");

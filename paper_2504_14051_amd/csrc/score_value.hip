@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
   float lse[8];
 #pragma unroll
   for (int r = 0; r < 8; ++r)
-    lse[r] = p.small_r && r < p.R ? p.lse2[(int64_t)bh * p.Rp + r] : INFINITY;
+    lse[r] = p.small_r && r < p.R ? row_lse2(p, b, hk, bh, r) : INFINITY;
 
   const T* Vb = reinterpret_cast<const T*>(p.V) + (int64_t)b * p.vsb + (int64_t)hk * p.vsh + tl * 8;
   float* h = p.h + (int64_t)bh * p.cap;

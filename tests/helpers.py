@@ -34,8 +34,28 @@ def to_device(cache, device="cuda"):
         seq_lens=None if cache.seq_lens is None else cache.seq_lens.to(device))
 
 
-def oracle_scores(oracle, cache, variant=0, threads=None):
-    """Oracle on the exact stored values.  Returns (c, h, a) as fp64 [B,Hkv,cap]."""
+def oracle_row_lse(oracle, cache):
+    """What the caller's attention pass would hand over: natural-log normaliser of every
+    window query row, [B, Hq, W] fp64, from the oracle's definition."""
+    wl = cache.wl
+    q = cache.q.cpu().double().numpy()
+    K = cache.K.cpu().double().numpy()
+    G = wl.n_q_heads // wl.n_kv_heads
+    out = np.zeros((q.shape[0], wl.n_q_heads, wl.window))
+    for b, N in enumerate(lengths(cache)):
+        for hk in range(wl.n_kv_heads):
+            if N <= 0:
+                continue
+            qg = q[b, hk * G:(hk + 1) * G].reshape(G * wl.window, -1)
+            out[b, hk * G:(hk + 1) * G] = oracle.row_lse(
+                qg, K[b, hk, :N], G, wl.window, float(np.float32(wl.softmax_scale)),
+                wl.window_in_cache).reshape(G, wl.window)
+    return out
+
+
+def oracle_scores(oracle, cache, variant=0, threads=None, lse=None):
+    """Oracle on the exact stored values.  Returns (c, h, a) as fp64 [B,Hkv,cap].
+    lse: row normalisers [B,Hq,W] to use instead of the oracle's own softmax."""
     wl = cache.wl
     lens = None if cache.seq_lens is None else cache.seq_lens.cpu().numpy()
     return oracle.score_batched(
@@ -45,7 +65,7 @@ def oracle_scores(oracle, cache, variant=0, threads=None):
         n_kv_heads=wl.n_kv_heads, window=wl.window, scale=float(np.float32(wl.softmax_scale)),
         window_in_cache=wl.window_in_cache, base=wl.base, pool_kernel=wl.pool_kernel,
         n_protect_head=wl.n_protect_head, n_protect_tail=wl.n_protect_tail, fast=bool(variant),
-        threads=threads or host_threads())
+        threads=threads or host_threads(), lse=lse)
 
 
 def lengths(cache):

@@ -18,11 +18,13 @@ def B():
     return binding
 
 
-def run_path(B, cache, budget, mode=0, variant=0, fused=False):
-    """Runs score -> select -> compact on the device.  Returns host copies of every stage."""
+def run_path(B, cache, budget, mode=0, variant=0, fused=False, row_lse=None):
+    """Runs score -> select -> compact on the device.  Returns host copies of every stage.
+    row_lse: fp32 host tensor [B,Hq,W] handed over as the caller's softmax normalisers."""
     wl = cache.wl
     dev = H.to_device(cache)
-    L = B.layout_for(wl, dev)
+    lse_dev = None if row_lse is None else row_lse.cuda()
+    L = B.layout_for(wl, dev, row_lse=lse_dev)
     L.variant = variant
     nb = B.caote_workspace_bytes(L, budget)
     ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
@@ -46,11 +48,13 @@ def run_path(B, cache, budget, mode=0, variant=0, fused=False):
     return out
 
 
-def full_check(B, oracle, cache, budget, mode=0, variant=0):
+def full_check(B, oracle, cache, budget, mode=0, variant=0, row_lse=None):
+    """row_lse: fp32 [B,Hq,W] normalisers that both sides take as given."""
     wl = cache.wl
     rtol = H.RTOL[wl.dtype]
-    res = run_path(B, cache, budget, mode, variant)
-    oc, oh, oa = H.oracle_scores(oracle, cache, variant)
+    res = run_path(B, cache, budget, mode, variant, row_lse=row_lse)
+    oc, oh, oa = H.oracle_scores(oracle, cache, variant,
+                                 lse=None if row_lse is None else row_lse.double().numpy())
     worst = H.check_scores(res["scores"], oc, oh, cache, rtol)
     H.check_kept(res["kept"], oc, cache, budget, rtol, gpu_scores=res["scores"])
     if wl.base == synth.BASE_H2O:        # the accumulator now holds h for every row
@@ -64,7 +68,7 @@ def full_check(B, oracle, cache, budget, mode=0, variant=0):
     for b, N in enumerate(H.lengths(cache)):
         assert np.isnan(res["scores"][b, :, N:]).all()
     # the fused entry point gives the same bits
-    fz = run_path(B, cache, budget, mode, variant, fused=True)
+    fz = run_path(B, cache, budget, mode, variant, fused=True, row_lse=row_lse)
     for key in ("scores", "kept"):
         assert np.array_equal(res[key], fz[key], equal_nan=True), f"caote_evict differs in {key}"
     for b, N in enumerate(H.lengths(cache)):
@@ -98,6 +102,14 @@ def test_llama3_8b_4k_h2o(B, oracle):
 def test_llama3_8b_32k_snapkv(B, oracle):
     wl = synth.llama3_8b_32k()
     full_check(B, oracle, synth.make_cache(wl), wl.budget)
+
+
+def test_llama3_8b_32k_snapkv_given_row_normalisers(B, oracle):
+    """The benchmark's second figure: the 32k layer with layout.row_lse set."""
+    wl = synth.llama3_8b_32k()
+    cache = synth.make_cache(wl)
+    lse = torch.from_numpy(H.oracle_row_lse(oracle, cache)).float()
+    full_check(B, oracle, cache, wl.budget, row_lse=lse)
 
 
 def test_qwen25_7b_128k_snapkv(B, oracle):
@@ -145,6 +157,27 @@ def test_small_shapes_ragged(B, oracle, kw):
     lens = np.array([wl.context, 333], dtype=np.int32)
     cache = synth.make_cache(wl, seq_lens=lens, base_init="random")
     full_check(B, oracle, cache, wl.budget)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(window=64),                                   # R = 256: eight-wave matrix-core sweep
+    dict(window=32, base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=32),   # R = 128
+    dict(window=8),                                    # R = 32
+    dict(window=1, budget=699),                        # R = 4: few-row path, evict one
+    dict(window=3, n_q_heads=8, n_kv_heads=2),         # R = 12: vector-ALU sweeps
+    dict(dtype="f32", head_dim=64, window=4),          # fp32
+], ids=["r256", "r128-snapkv", "r32", "r4", "r12", "f32"])
+@pytest.mark.parametrize("shift", [0.0, 0.6931471805599453], ids=["exact", "shifted"])
+def test_row_normalisers_from_the_caller(B, oracle, kw, shift):
+    """The first key sweep is skipped when the layout carries row_lse.  Both sides take the
+    same fp32 normalisers as given: the oracle's own, or those shifted by ln 2 (which halves
+    every attention mass: nothing is renormalised behind the caller's back)."""
+    wl = small(**kw)
+    lens = np.array([wl.context, 333], dtype=np.int32)
+    cache = synth.make_cache(wl, seq_lens=lens, base_init="random")
+    lse = torch.from_numpy(H.oracle_row_lse(oracle, cache) + shift).float()
+    mode = 1 if wl.window == 1 else 0
+    full_check(B, oracle, cache, wl.budget, mode=mode, row_lse=lse)
 
 
 def test_fastcaote_variant(B, oracle):
