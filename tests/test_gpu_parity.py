@@ -180,6 +180,18 @@ def test_row_normalisers_from_the_caller(B, oracle, kw, shift):
     full_check(B, oracle, cache, wl.budget, mode=mode, row_lse=lse)
 
 
+@pytest.mark.parametrize("pool", [1, 33, 127, 129, 131, 301])
+@pytest.mark.parametrize("window", [8, 64])
+def test_snapkv_pool_widths(B, oracle, pool, window):
+    """Pooling half-widths up to and beyond what the fused second sweep carries (64 keys), with
+    splits shorter than the window they pool over; the widest ones fall back to the separate
+    value-sum kernel."""
+    wl = small(base=synth.BASE_SNAPKV, pool_kernel=pool, window=window, n_protect_tail=window,
+               n_protect_head=3, context=1500, budget=400)
+    lens = np.array([wl.context, 1500 - 257], dtype=np.int32)
+    full_check(B, oracle, synth.make_cache(wl, seq_lens=lens), wl.budget)
+
+
 def test_fastcaote_variant(B, oracle):
     wl = small(base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=8)
     full_check(B, oracle, synth.make_cache(wl), wl.budget, variant=1)
