@@ -138,6 +138,11 @@ def main():
         q = torch.roll(host.q, sh * G, dims=1).cuda()
         base = torch.roll(host.base, sh, dims=1).cuda() if wl.base == synth.BASE_H2O else None
         layers.append((q, K, V, base))
+    # Block-wise prefill: every step first appends the block (here: the rows the generator put
+    # last, from a buffer of their own) behind the budget of kept rows, then evicts.
+    blockwise = wl.name.endswith("prefill-block")
+    blocks = [(K[:, :, -wl.window:].contiguous(), V[:, :, -wl.window:].contiguous())
+              for (_, K, V, _) in layers] if blockwise else None
     q0, K0, V0, _ = layers[0]
     L = B.make_layout(q0, K0, V0, base=wl.base, softmax_scale=wl.softmax_scale,
                       window_in_cache=wl.window_in_cache, pool_kernel=wl.pool_kernel,
@@ -155,8 +160,15 @@ def main():
     torch.cuda.synchronize()
     del calib_src, calib_dst
 
+    def append(i):
+        if blockwise:
+            _, K, V, base = layers[i % n_layers]
+            k_new, v_new = blocks[i % n_layers]
+            B.caote_append(K, V, base, k_new, v_new, L, wl.budget, wl.window, stream)
+
     def step(i):
         q, K, V, base = layers[i % n_layers]
+        append(i)
         B.caote_evict(q, K, V, base, L, wl.budget, mode, scores, kept, ws, stream)
 
     # The same path when the caller's attention pass hands its softmax normalisers over
@@ -185,6 +197,7 @@ def main():
 
     def step_lse(i):
         q, K, V, base = layers[i % n_layers]
+        append(i)
         B.caote_evict(q, K, V, base, lse_layouts[i % n_layers][1], wl.budget, mode, scores, kept, ws, stream)
 
     def timed_replay(step_fn):
@@ -257,7 +270,7 @@ def main():
                    "head_dim": wl.head_dim, "context": wl.context, "window": wl.window,
                    "budget": wl.budget, "base": {0: "none", 1: "h2o", 2: "snapkv"}[wl.base],
                    "pool_kernel": wl.pool_kernel, "batch": wl.batch, "layer_buffers": n_layers,
-                   "entry_point": "caote_evict",
+                   "entry_point": "caote_append + caote_evict" if blockwise else "caote_evict",
                    "launch": "stream" if args.no_graph else "hip_graph"},
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,

@@ -147,6 +147,21 @@ caote_status caote_compact(void* K, void* V, float* base_score,
                            int32_t budget, int32_t mode, void* workspace,
                            size_t workspace_bytes, void* hip_stream);
 
+/* Block-wise prefill with eviction (Sec. 2, block-wise prefill: the new block's keys
+ * and values join the cache, K = [K_{:t}, K_{t+1:t+m}]; Sec. 4 uses blocks of 128):
+ * copies `n_new` rows per (sequence, KV head) from k_new / v_new into K / V behind
+ * the rows the sequence holds, i.e. into rows [N_b, N_b + n_new) with N_b =
+ * seq_lens[b], or N_b = `n_at` for every sequence when seq_lens is NULL, and sets
+ * the appended rows of base_score (if not NULL) to 0: a token that no query has
+ * looked at yet has no accumulated attention.  Rows that would fall beyond
+ * `capacity` are dropped.  The caller then raises its seq_lens by n_new and calls
+ * caote_evict with the block's queries as the window.
+ *   k_new, v_new  DEVICE [batch][n_kv_heads][n_new][head_dim], dense, layout dtype.
+ * q_stride_* , window, base and the other scoring fields of the layout are not used. */
+caote_status caote_append(void* K, void* V, float* base_score, const void* k_new,
+                          const void* v_new, const caote_layout* layout, int32_t n_at,
+                          int32_t n_new, void* hip_stream);
+
 /* caote_score + caote_select + caote_compact in one stream-ordered call, with the
  * same results as the three calls in sequence.  `scores` and `kept_idx` are
  * outputs as above.                                                                */

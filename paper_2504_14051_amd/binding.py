@@ -22,7 +22,7 @@ EXACT, FAST = 0, 1
 COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
 
 EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
-           "caote_evict", "caote_evict_timed", "caote_phase_name", "caote_last_error",
+           "caote_append", "caote_evict", "caote_evict_timed", "caote_phase_name", "caote_last_error",
            "caote_version")
 MAX_PHASES = 16
 
@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.caote_select.restype = ctypes.c_int
         L.caote_compact.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, sz, vp]
         L.caote_compact.restype = ctypes.c_int
+        L.caote_append.argtypes = [vp, vp, vp, vp, vp, lp, i32, i32, vp]
+        L.caote_append.restype = ctypes.c_int
         L.caote_evict.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp]
         L.caote_evict.restype = ctypes.c_int
         L.caote_evict_timed.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp,
@@ -165,6 +167,12 @@ def caote_compact(K, V, base_score, kept_idx, layout: Layout, budget: int, mode,
     _check(lib().caote_compact(_ptr(K), _ptr(V), _ptr(base_score), _ptr(kept_idx),
                                ctypes.byref(layout), budget, mode, _ptr(workspace), wb,
                                _stream(stream)))
+
+
+def caote_append(K, V, base_score, k_new, v_new, layout: Layout, n_at: int, n_new: int,
+                 stream=None) -> None:
+    _check(lib().caote_append(_ptr(K), _ptr(V), _ptr(base_score), _ptr(k_new), _ptr(v_new),
+                              ctypes.byref(layout), n_at, n_new, _stream(stream)))
 
 
 def caote_evict(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores, kept_idx,

@@ -234,6 +234,26 @@ caote_status caote_compact(void* K, void* V, float* base_score, const int32_t* k
   return device_status(caote::launch_compact(p, (hipStream_t)hip_stream, nullptr), "compact");
 }
 
+caote_status caote_append(void* K, void* V, float* base_score, const void* k_new,
+                          const void* v_new, const caote_layout* layout, int32_t n_at,
+                          int32_t n_new, void* hip_stream) {
+  caote_status st = check_layout(layout, 0, false);
+  if (st != CAOTE_OK) return st;
+  if (!K || !V || !k_new || !v_new) return fail(CAOTE_EINVAL, "K, V, k_new and v_new must not be NULL");
+  if (n_new < 0) return fail(CAOTE_EINVAL, "n_new must be >= 0");
+  if (!layout->seq_lens && (n_at < 0 || (int64_t)n_at + n_new > layout->capacity))
+    return fail(CAOTE_EINVAL, "rows [%d, %d) do not fit the capacity %d", n_at, n_at + n_new,
+                layout->capacity);
+  if (((uintptr_t)k_new | (uintptr_t)v_new) % 16 != 0)
+    return fail(CAOTE_EINVAL, "k_new and v_new must be 16-byte aligned");
+  if (n_new == 0) return CAOTE_OK;
+  Params p;
+  plan(layout, 0, p, nullptr);
+  p.K = K; p.V = V; p.base = base_score;
+  return device_status(caote::launch_append(p, k_new, v_new, n_at, n_new, (hipStream_t)hip_stream),
+                       "append");
+}
+
 static caote_status evict_impl(const void* q_window, void* K, void* V, float* base_score,
                                const caote_layout* layout, int32_t budget, int32_t mode,
                                float* scores, int32_t* kept_idx, void* workspace,

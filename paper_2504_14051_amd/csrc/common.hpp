@@ -137,5 +137,7 @@ hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_append(const Params& p, const void* k_new, const void* v_new, int n_at, int n_new,
+                         hipStream_t s);
 
 }  // namespace caote

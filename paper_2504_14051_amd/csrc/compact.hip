@@ -95,7 +95,39 @@ __global__ __launch_bounds__(kThreads) void k_move_rows(const Params p, int row_
   }
 }
 
+// Block-wise prefill (Sec. 2): the new block's rows go behind the rows a sequence holds.
+// One thread per 16-byte chunk of a new row; K and V in the same pass.
+__global__ __launch_bounds__(kThreads) void k_append(const Params p, const char* k_new, const char* v_new,
+                                                     int n_at, int n_new, int row_bytes) {
+  const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
+  const int cpr = row_bytes / 16;
+  const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  const int i = (int)(id / cpr), ch = (int)(id % cpr);
+  if (i >= n_new) return;
+  int at = n_at;
+  if (p.seq_lens) { at = p.seq_lens[b]; at = at < 0 ? 0 : at; }
+  const int row = at + i;
+  if (row >= p.cap) return;                           // does not fit: dropped
+  const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
+  char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
+  char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
+  const int64_t src = ((int64_t)bh * n_new + i) * row_bytes + ch * 16;
+  *reinterpret_cast<uint4*>(Kb + row * p.ksn * esz + ch * 16) = *reinterpret_cast<const uint4*>(k_new + src);
+  *reinterpret_cast<uint4*>(Vb + row * p.vsn * esz + ch * 16) = *reinterpret_cast<const uint4*>(v_new + src);
+  if (ch == 0 && p.base) p.base[(int64_t)bh * p.cap + row] = 0.f;
+}
+
 }  // namespace
+
+hipError_t launch_append(const Params& p, const void* k_new, const void* v_new, int n_at, int n_new,
+                         hipStream_t s) {
+  const int row_bytes = p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
+  const int64_t chunks = (int64_t)n_new * (row_bytes / 16);
+  const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads), p.B * p.Hkv);
+  hipLaunchKernelGGL(k_append, grid, dim3(kThreads), 0, s, p, reinterpret_cast<const char*>(k_new),
+                     reinterpret_cast<const char*>(v_new), n_at, n_new, row_bytes);
+  return hipGetLastError();
+}
 
 hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int row_bytes = p.D * (p.dtype == CAOTE_F32 ? 4 : 2);

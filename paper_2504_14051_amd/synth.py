@@ -85,12 +85,21 @@ def decode_step(batch: int = 16) -> Workload:
                     seed=20250418)
 
 
+def prefill_block(batch: int = 1) -> Workload:
+    """One step of block-wise prefill with eviction (Sec. 2, block-wise prefill; Sec. 4 set-up):
+    the cache holds its budget of 2048 tokens plus the block of 128 just appended, the block's
+    128 query positions form the window, and 128 tokens are evicted."""
+    return Workload("llama3-8b-prefill-block", batch, 32, 8, 128, "bf16", 2048 + 128, 128, 2048,
+                    BASE_H2O, seed=20250419)
+
+
 WORKLOADS = {
     "tiny": tiny,
     "llama3-8b-4k": llama3_8b_4k,
     "llama3-8b-32k": llama3_8b_32k,
     "qwen2.5-7b-128k": qwen25_7b_128k,
     "llama3-8b-decode": decode_step,
+    "llama3-8b-prefill-block": prefill_block,
 }
 
 

@@ -124,3 +124,21 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libcaote_hip.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         binding.lib()
+
+
+def test_append_arguments_are_checked_on_the_host(B):
+    L = good_layout(B)
+    fake = 0x1000
+    with pytest.raises(B.CaoteError) as e:                       # rows do not fit
+        B.caote_append(fake, fake, None, fake, fake, L, L.capacity - 3, 4, stream=0)
+    assert e.value.status == B.EINVAL and "capacity" in str(e.value)
+    with pytest.raises(B.CaoteError) as e:                       # null source
+        B.caote_append(fake, fake, None, None, fake, L, 0, 4, stream=0)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.CaoteError) as e:                       # misaligned source
+        B.caote_append(fake, fake, None, fake + 8, fake, L, 0, 4, stream=0)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.CaoteError) as e:
+        B.caote_append(fake, fake, None, fake, fake, L, 0, -1, stream=0)
+    assert e.value.status == B.EINVAL
+    B.caote_append(fake, fake, None, fake, fake, L, 0, 0, stream=0)   # nothing to do: no launch

@@ -133,6 +133,68 @@ def test_decode_stream_steps(B, oracle):
         cache = synth.Cache(wl, fresh.q, K, V, base, None)
 
 
+def test_append_rows_behind_each_sequence(B):
+    """caote_append against plain tensor assignment: ragged lengths, a strided cache, rows that
+    do not fit are dropped, the accumulator of the new rows is zero."""
+    torch.manual_seed(5)
+    Bn, Hkv, cap, d, n_new = 3, 2, 40, 128, 6
+    big = torch.randn(Bn, Hkv, cap, 2 * d, device="cuda").to(torch.bfloat16)
+    K, V = big[..., :d], big[..., d:]                      # row stride 2 d: strided views
+    base = torch.rand(Bn, Hkv, cap, device="cuda")
+    k_new = torch.randn(Bn, Hkv, n_new, d, device="cuda").to(torch.bfloat16)
+    v_new = torch.randn(Bn, Hkv, n_new, d, device="cuda").to(torch.bfloat16)
+    q = torch.zeros(Bn, Hkv, 1, d, device="cuda", dtype=torch.bfloat16)
+    lens = torch.tensor([10, 34, 37], dtype=torch.int32, device="cuda")   # the last one overflows
+    Kr, Vr, br = K.clone(), V.clone(), base.clone()
+    for b, n in enumerate(lens.tolist()):
+        m = min(n_new, cap - n)
+        Kr[b, :, n:n + m], Vr[b, :, n:n + m], br[b, :, n:n + m] = k_new[b, :, :m], v_new[b, :, :m], 0.0
+    L = B.make_layout(q, K, V, base=synth.BASE_H2O, softmax_scale=0.1, seq_lens=lens)
+    B.caote_append(K, V, base, k_new, v_new, L, 0, n_new)
+    torch.cuda.synchronize()
+    assert torch.equal(K.view(torch.int16), Kr.view(torch.int16)) and torch.equal(V.view(torch.int16), Vr.view(torch.int16))
+    assert torch.equal(base, br)
+    # uniform position, no accumulator
+    L2 = B.make_layout(q, K, V, base=synth.BASE_NONE, softmax_scale=0.1)
+    B.caote_append(K, V, None, k_new, v_new, L2, 20, n_new)
+    torch.cuda.synchronize()
+    Kr[:, :, 20:26], Vr[:, :, 20:26] = k_new, v_new
+    assert torch.equal(K.view(torch.int16), Kr.view(torch.int16)) and torch.equal(V.view(torch.int16), Vr.view(torch.int16))
+    assert torch.equal(base, br)
+
+
+def test_blockwise_prefill_stream(B, oracle):
+    """Block-wise prefill with eviction (Sec. 2; Sec. 4 set-up, scaled down): blocks of 32 new
+    tokens join a cache held at a budget of 256, the block's queries are the window, the H2O
+    accumulator is carried, 32 tokens are evicted per block.  Each block is checked against
+    the oracle started from the GPU's state, so rounding does not pile up."""
+    wl = small(batch=2, context=256 + 32, window=32, budget=256, base=synth.BASE_H2O)
+    cache = synth.make_cache(wl, base_init="random")
+    dev = H.to_device(cache)
+    ws = scores = kept = None
+    for block in range(4):
+        fresh = synth.make_cache(wl, layer=block + 1)
+        k_new = fresh.K[:, :, -wl.window:].contiguous().cuda()
+        v_new = fresh.V[:, :, -wl.window:].contiguous().cuda()
+        L = B.layout_for(wl, dev)
+        # append on the device, and the same by assignment for the oracle's input
+        B.caote_append(dev.K, dev.V, dev.base, k_new, v_new, L, wl.budget, wl.window)
+        torch.cuda.synchronize()
+        host = synth.Cache(wl, fresh.q, dev.K.cpu(), dev.V.cpu(), dev.base.cpu(), None)
+        assert torch.equal(host.K[:, :, wl.budget:].view(torch.int16), fresh.K[:, :, -wl.window:].view(torch.int16))
+        assert (host.base[:, :, wl.budget:] == 0).all()
+        full_check(B, oracle, host, wl.budget)
+        # carry the GPU's own state on: evict on the device tensors
+        dev = synth.Cache(wl, fresh.q.cuda(), dev.K, dev.V, dev.base, None)
+        L = B.layout_for(wl, dev)
+        if ws is None:
+            ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
+            scores = torch.empty(wl.batch, wl.n_kv_heads, wl.context, device="cuda")
+            kept = torch.empty(wl.batch, wl.n_kv_heads, wl.budget, dtype=torch.int32, device="cuda")
+        B.caote_evict(dev.q, dev.K, dev.V, dev.base, L, wl.budget, 0, scores, kept, ws)
+        torch.cuda.synchronize()
+
+
 # ---- shapes, modes, edges -------------------------------------------------------------
 
 @pytest.mark.parametrize("kw", [
