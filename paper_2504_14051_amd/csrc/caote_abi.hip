@@ -95,7 +95,7 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.use_mfma = p.dtype == CAOTE_BF16 && p.D == 128 && p.R > 16;
   p.small_r = !p.use_mfma && p.R <= 8;
   p.s_rows = p.R <= 4 ? 4 : 8;
-  p.split_len = p.use_mfma ? chunk_len(p.R > 128 ? 256 : 512, 128, 1 << 20) : chunk_len(1024, 256, 8192);
+  p.split_len = p.use_mfma ? chunk_len(p.R > 128 ? 256 : 512, 128, 1 << 20) : (p.R <= 8 ? chunk_len(2048, 128, 8192) : chunk_len(1024, 256, 8192));
   p.n_split = ceil_div(p.cap, p.split_len);
   p.vchunk_len = caote::kVChunk;
   p.n_vchunk = ceil_div(p.cap, p.vchunk_len);
