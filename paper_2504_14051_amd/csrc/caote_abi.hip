@@ -95,7 +95,9 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.use_mfma = p.dtype == CAOTE_BF16 && p.D == 128 && p.R > 16;
   p.small_r = !p.use_mfma && p.R <= 8;
   p.s_rows = p.R <= 4 ? 4 : 8;
-  p.split_len = p.use_mfma ? chunk_len(p.R > 128 ? 256 : 512, 128, 1 << 20) : (p.R <= 8 ? chunk_len(2048, 128, 8192) : chunk_len(1024, 256, 8192));
+  p.s_pitch = (int)align_up((size_t)p.cap, 4);
+  p.split_len = p.use_mfma ? chunk_len(p.R > 128 ? 256 : 512, 128, 1 << 20) : (p.R <= 8 ? (p.dtype == CAOTE_BF16 && p.D == 128 ? chunk_len(768, 128, 8192) : chunk_len(2048, 128, 8192))
+                           : chunk_len(1024, 256, 8192));
   p.n_split = ceil_div(p.cap, p.split_len);
   p.vchunk_len = caote::kVChunk;
   p.n_vchunk = ceil_div(p.cap, p.vchunk_len);
@@ -110,7 +112,7 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return ws ? ws + o : nullptr; };
   p.stats = (float*)carve((size_t)BH * p.n_split * p.Rp * 2 * sizeof(float));
   p.lse2 = (float*)carve((size_t)BH * p.Rp * sizeof(float));
-  p.S = (float*)carve(p.small_r ? (size_t)BH * p.cap * p.s_rows * sizeof(float) : 0);
+  p.S = (float*)carve(p.small_r ? (size_t)BH * p.s_pitch * p.s_rows * sizeof(float) : 0);
   p.a = (float*)carve((size_t)BH * p.cap * sizeof(float));
   p.h = (float*)carve((size_t)BH * p.cap * sizeof(float));
   p.opart = (float*)carve((size_t)BH * p.n_vpart * p.D * sizeof(float));
@@ -143,7 +145,8 @@ caote_status device_status(hipError_t e, const char* what) {
 
 caote_status do_score(Params& p, hipStream_t s, caote::PhaseHook* hook = nullptr) {
   hipError_t e = p.use_mfma   ? caote::launch_score_mfma(p, s, hook)
-                 : p.small_r  ? caote::launch_score_small(p, s, hook)
+                 : p.small_r  ? (p.dtype == CAOTE_BF16 && p.D == 128 ? caote::launch_score_few_mfma(p, s, hook)
+                                                                    : caote::launch_score_small(p, s, hook))
                               : caote::launch_score_generic(p, s, hook);
   if (e != hipSuccess) return device_status(e, "score (key sweeps)");
   return device_status(caote::launch_value_passes(p, s, hook), "score (value sweeps)");

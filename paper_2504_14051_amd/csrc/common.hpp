@@ -35,8 +35,9 @@ struct Params {
   // ---- workspace ----
   float* stats;       // [BH][n_split][Rp][2]  partial (max, sum) per query row
   float* lse2;        // [BH][Rp]              log2-sum-exp2 per query row
-  float* S;           // [BH][cap][s_rows]     stored logits (few-row path only)
+  float* S;           // [BH][s_rows][s_pitch] stored logits (few-row path only)
   int small_r, s_rows;// few-row path: R <= 8, logits kept instead of a second key sweep
+  int s_pitch;        // cap rounded up to a multiple of 4 (16-byte aligned rows of S)
   float* a;           // [BH][cap]             column sums of attention
   float* h;           // [BH][cap]             base score (aliases `base` for H2O)
   float* opart;       // [BH][n_vpart][D]      partial sum of h_j v_j
@@ -133,6 +134,7 @@ inline void mark(PhaseHook* h, const char* name) { if (h) h->mark(name); }
 hipError_t launch_score_generic(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_score_mfma(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_score_small(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook);

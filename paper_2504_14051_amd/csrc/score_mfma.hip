@@ -487,7 +487,155 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_stats_wave(const Params
   if (lane == 0) p.lse2[(int64_t)bh * p.Rp + r] = L > 0.f ? M + log2f(L) : INFINITY;
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Few query rows (R <= 8: decode-time eviction, Sec. 2 generation) on the matrix cores.
+// One sweep over K that stores the scaled logits (see score_small.hip for why) and keeps the
+// running (max, sum) of each row.  The R rows are padded to one 32-row block: the MFMA does
+// the 128-long dot products and their reduction, which on the vector ALUs cost 25
+// instructions per key; the padding is free, the matrix pipe is idle otherwise.
+// Every wave works alone: it fetches its own 32-key blocks into a private ring of LDS slots
+// (DMA, swizzled), so there is no barrier in the loop.  Keys on M, rows on N: lane l holds
+// 16 keys of row l % 32, and only lanes with l % 32 < R carry anything.
+// ---------------------------------------------------------------------------------------
+constexpr int kFewWaves = 2;              // waves per workgroup
+constexpr int kFewSlots = 3;              // LDS slots (8 KiB) per wave: two blocks in flight
+constexpr int kFewBlock = 32;             // keys per block
+
+__global__ __launch_bounds__(kFewWaves * kWave) void k_rowstats_few_mfma(const Params p) {
+  const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
+  const int N = seq_len(p, b);
+  const int c0 = blockIdx.x * p.split_len;
+  if (blockIdx.x == 0 && p.lse_in) reset_counters(p, bh);   // no merge kernel follows then
+  if (c0 >= N) return;
+  const int c1 = min(N, c0 + p.split_len);
+  const int nblk = (c1 - c0 + kFewBlock - 1) / kFewBlock;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int P = p.wic ? N - p.W : N;
+  const int n = lane & 31;                // query row of this lane
+
+  __shared__ __attribute__((aligned(16))) unsigned char ring[kFewWaves][kFewSlots][kFewBlock * kRowBytes];
+  __shared__ float st_lds[kFewWaves][8][2];
+
+  const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.K) +
+                            ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * 2;
+  const int64_t krow = p.ksn * 2;
+  // block i of this wave is block wave + kFewWaves * i of the chunk
+  const int my_blocks = nblk > wave ? (nblk - wave + kFewWaves - 1) / kFewWaves : 0;
+  auto issue = [&](int i, int slot) {
+    const int j0 = c0 + (wave + kFewWaves * i) * kFewBlock;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s16 = u * kWave + lane;                       // 16-byte slot inside the block
+      const int row = s16 / kChunks, pc = s16 % kChunks;
+      const int j = min(j0 + row, N - 1);                     // rows past the end repeat the last one
+      load_to_lds16(Kb + j * krow + ((pc ^ (row & 15)) << 4),
+                    __builtin_amdgcn_readfirstlane(lds_addr(&ring[wave][slot][u * kWave * 16])));
+    }
+  };
+  for (int i = 0; i < kFewSlots - 1 && i < my_blocks; ++i) issue(i, i);
+
+  bf16x8 qf[8];
+  int nvis = 0;                           // keys visible to this lane's row (0: no such row)
+  if (n < p.R) {
+    int g, iw;
+    divmod_w(p, n, g, iw);
+    const unsigned char* qp = reinterpret_cast<const unsigned char*>(p.q) +
+        ((int64_t)b * p.qsb + (int64_t)(hk * p.G + g) * p.qsh + (int64_t)iw * p.qsw) * 2 + (lane >> 5) * 16;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + ks * 32));
+    nvis = p.wic ? P + iw + 1 : N;
+  } else {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = __builtin_bit_cast(bf16x8, make_uint4(0, 0, 0, 0));
+  }
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) asm volatile("" : : "v"(qf[ks]));   // the compiler's waits end here
+
+  float* Srow = p.S + ((int64_t)bh * p.s_rows + n) * p.s_pitch;      // row n of the stored logits
+  float m_run = -INFINITY, l_run = 0.f;
+  int slot = 0;
+  for (int i = 0; i < my_blocks; ++i) {
+    const int ahead = min(kFewSlots - 2, my_blocks - 1 - i);         // blocks requested after block i
+    if (i + kFewSlots - 1 < my_blocks) issue(i + kFewSlots - 1, slot == 0 ? kFewSlots - 1 : slot - 1);
+    // (the slot of block i-1: this wave has read it)
+    if (i + kFewSlots - 1 < my_blocks) wait_vmcnt<(kFewSlots - 1) * 8>();
+    else if (ahead >= 1) wait_vmcnt<8>();
+    else wait_vmcnt<0>();
+    const unsigned char* tile = &ring[wave][slot][0];
+    bf16x8 kf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+      kf[ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(&tile[swz(n, 2 * ks + (lane >> 5))]));
+    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks], qf[ks], acc, 0, 0, 0);
+    const int jb = c0 + (wave + kFewWaves * i) * kFewBlock;
+    float t[16];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int j = jb + m_of(e, lane);
+      t[e] = (j < c1 && j < nvis) ? acc[e] * p.c2 : -INFINITY;
+      mx = fmaxf(mx, t[e]);
+    }
+    if (n < p.s_rows) {                    // rows R..s_rows-1 are stored as -inf: exp2 gives 0
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {     // four consecutive keys per store
+        const int j = jb + 8 * g4 + 4 * (lane >> 5);
+        if (j + 3 < c1) {
+          *reinterpret_cast<float4*>(Srow + j) = make_float4(t[4 * g4], t[4 * g4 + 1], t[4 * g4 + 2], t[4 * g4 + 3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (j + e < c1) Srow[j + e] = t[4 * g4 + e];
+        }
+      }
+    }
+    const float mn = fmaxf(m_run, mx);
+    if (mn > -INFINITY) {
+      float ssum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) ssum += __builtin_amdgcn_exp2f(t[e] - mn);
+      l_run = l_run * __builtin_amdgcn_exp2f(m_run - mn) + ssum;
+      m_run = mn;
+    }
+    slot = slot + 1 == kFewSlots ? 0 : slot + 1;
+  }
+  // ---- the two half-waves, then the waves ------------------------------------------------------
+  {
+    const float m2 = __shfl_xor(m_run, 32, kWave), l2 = __shfl_xor(l_run, 32, kWave);
+    const float M = fmaxf(m_run, m2);
+    float L = 0.f;
+    if (m_run > -INFINITY) L += l_run * exp2f(m_run - M);
+    if (m2 > -INFINITY) L += l2 * exp2f(m2 - M);
+    if (lane < 8) { st_lds[wave][lane][0] = M; st_lds[wave][lane][1] = L; }
+  }
+  __syncthreads();
+  if (tid < p.R) {
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < kFewWaves; ++w) M = fmaxf(M, st_lds[w][tid][0]);
+    float L = 0.f;
+#pragma unroll
+    for (int w = 0; w < kFewWaves; ++w)
+      if (st_lds[w][tid][0] > -INFINITY) L += st_lds[w][tid][1] * exp2f(st_lds[w][tid][0] - M);
+    float* st = p.stats + (((int64_t)bh * p.n_split + blockIdx.x) * p.Rp + tid) * 2;
+    st[0] = M; st[1] = L;
+  }
+}
+
 }  // namespace
+
+// Few-row key sweep on the matrix cores.  Requires: bf16, head_dim 128, R <= 8, split_len a
+// multiple of 32.
+hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook) {
+  hipLaunchKernelGGL(k_rowstats_few_mfma, dim3(p.n_split, p.B * p.Hkv), dim3(kFewWaves * kWave), 0, s, p);
+  mark(hook, "key_rowstats");
+  if (p.lse_in) return hipGetLastError();   // the caller's normalisers: nothing to merge
+  return launch_merge_stats(p, s, hook);
+}
+
 
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook) {
   hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kMergeThreads), 0, s, p);

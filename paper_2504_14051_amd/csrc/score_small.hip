@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void k_rowstats_small(const Params p) {
     }
   }
   const T* Kb = reinterpret_cast<const T*>(p.K) + (int64_t)b * p.ksb + (int64_t)hk * p.ksh + tl * 8;
-  float* Sb = p.S + ((int64_t)bh * p.cap) * RT;
+  float* Sb = p.S + (int64_t)bh * RT * p.s_pitch;       // row r of the stored logits at Sb + r * s_pitch
   float m = -INFINITY, l = 0.f;
 
   for (int j0 = c0 + team; j0 < c1; j0 += KPI * kKeysInFlight) {
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void k_rowstats_small(const Params p) {
       }
       const bool vis = j < c1 && j < nvis_my && myr < p.R;
       t[u] = vis ? mine * p.c2 : -INFINITY;
-      if (j < c1 && tl < RT) Sb[(int64_t)j * RT + tl] = t[u];   // lane tl holds row tl
+      if (j < c1 && tl < RT) Sb[(int64_t)tl * p.s_pitch + j] = t[u];   // lane tl holds row tl
     }
     // one rescale of the running sum per step, not per key
     float mx = t[0];

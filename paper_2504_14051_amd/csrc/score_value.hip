@@ -49,16 +49,13 @@ __device__ __forceinline__ void widen(const Frag<float>& f, float (&x)[8]) {
 // the second key sweep, or, on the few-row path, from the stored logits.
 __device__ __forceinline__ float mass_of(const Params& p, int bh, int j, const float (&lse)[8]) {
   if (!p.small_r) return p.a[(int64_t)bh * p.cap + j];
-  const float* t = p.S + ((int64_t)bh * p.cap + j) * p.s_rows;
-  float a = 0.f;
-  if (p.s_rows == 4) {
-    const float4 v = *reinterpret_cast<const float4*>(t);
-    a = (__builtin_amdgcn_exp2f(v.x - lse[0]) + __builtin_amdgcn_exp2f(v.y - lse[1])) + (__builtin_amdgcn_exp2f(v.z - lse[2]) + __builtin_amdgcn_exp2f(v.w - lse[3]));
-  } else {
-    const float4 v = *reinterpret_cast<const float4*>(t), w = *reinterpret_cast<const float4*>(t + 4);
-    a = ((__builtin_amdgcn_exp2f(v.x - lse[0]) + __builtin_amdgcn_exp2f(v.y - lse[1])) + (__builtin_amdgcn_exp2f(v.z - lse[2]) + __builtin_amdgcn_exp2f(v.w - lse[3]))) +
-        ((__builtin_amdgcn_exp2f(w.x - lse[4]) + __builtin_amdgcn_exp2f(w.y - lse[5])) + (__builtin_amdgcn_exp2f(w.z - lse[6]) + __builtin_amdgcn_exp2f(w.w - lse[7])));
-  }
+  const float* t = p.S + (int64_t)bh * p.s_rows * p.s_pitch + j;      // row r of S at t + r * s_pitch
+  const int64_t sp = p.s_pitch;
+  float a = (__builtin_amdgcn_exp2f(t[0] - lse[0]) + __builtin_amdgcn_exp2f(t[sp] - lse[1])) +
+            (__builtin_amdgcn_exp2f(t[2 * sp] - lse[2]) + __builtin_amdgcn_exp2f(t[3 * sp] - lse[3]));
+  if (p.s_rows == 8)
+    a += (__builtin_amdgcn_exp2f(t[4 * sp] - lse[4]) + __builtin_amdgcn_exp2f(t[5 * sp] - lse[5])) +
+         (__builtin_amdgcn_exp2f(t[6 * sp] - lse[6]) + __builtin_amdgcn_exp2f(t[7 * sp] - lse[7]));
   return a;
 }
 
