@@ -61,21 +61,24 @@ __device__ __forceinline__ float mass_of(const Params& p, int bh, int j, const f
 
 template <typename T, int D>
 __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
-  constexpr int TL = D / 8;
-  constexpr int RPI = kThreads / TL;      // rows in flight per iteration
-  constexpr int ITER = kVChunk / RPI;     // iterations per chunk
-  static_assert(ITER % kUnroll == 0, "chunk must be a whole number of unrolled groups");
+  // Every wave owns 64 consecutive tokens of the chunk and works alone until the final
+  // reduction: lane l weighs token l of the wave's share, the weight then travels to the
+  // 16 (8) lanes that hold that token's value row by a lane shuffle.  No LDS and no barrier
+  // between the weights and the value rows, whose loads are requested first.
+  constexpr int TL = D / 8;               // lanes per value row
+  constexpr int RPW = kWave / TL;         // rows per wave per load instruction
+  constexpr int ITER = kWave / RPW;       // load instructions per wave per chunk (one per RPW rows)
+  constexpr int NW = kThreads / kWave;
+  static_assert(ITER % kUnroll == 0 && NW * kWave == kVChunk, "chunk geometry");
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
   const int w0 = blockIdx.x * p.vrep * kVChunk;          // first token of this workgroup
   if (w0 >= N) return;
-  const int tid = threadIdx.x, team = tid / TL, tl = tid % TL;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, tl = lane % TL, sub = lane / TL;
   const int lo = min(p.ph, N), hi = max(lo, N - p.pt);   // scored rows [lo,hi)
   const int half = p.pool / 2;
 
-  __shared__ float w_lds[kVChunk];        // weight of each row of the chunk in sum h_j v_j
-  __shared__ float red[RPI][D];
-  __shared__ float zred[kThreads / kWave];
+  __shared__ float red[NW][D + 1];
 
   // few-row path: normalisers of the (at most 8) query rows; rows that do not exist or see
   // no key have lse2 = +inf and stored logits -inf, both give exp2(-inf) = 0
@@ -90,16 +93,21 @@ __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
   float zsum = 0.f;
 
   for (int rep = 0; rep < p.vrep; ++rep) {
-    const int c0 = w0 + rep * kVChunk;
-    if (c0 >= N) break;
-    // ---- phase A: one thread per token: base score h_j ------------------------------
+    const int c0 = w0 + rep * kVChunk + wave * kWave;      // first token of this wave's share
+    if (c0 >= N) break;                                    // (wave-uniform; no barrier in the loop)
+    Frag<T> f[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int j = c0 + u * RPW + sub;
+      if (j < N) fetch(Vb + (int64_t)j * p.vsn, f[u]); else zero(f[u]);
+    }
+    // ---- the weight of token c0 + lane ------------------------------------------------------
+    float wj = 0.f;
     {
-      const int j = c0 + tid;
-      float hj = 0.f;
-      bool scored = false;
+      const int j = c0 + lane;
       if (j < N) {
-        scored = j >= lo && j < hi;
-        hj = mass_of(p, bh, j, lse);
+        const bool scored = j >= lo && j < hi;
+        float hj = mass_of(p, bh, j, lse);
         if (p.base_mode == CAOTE_BASE_H2O) {
           hj += h[j];                           // h aliases the accumulator
         } else if (p.base_mode == CAOTE_BASE_SNAPKV && scored) {
@@ -107,48 +115,47 @@ __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
           for (int t = t0; t <= t1; ++t) hj = fmaxf(hj, t == j ? hj : mass_of(p, bh, t, lse));
         }
         h[j] = hj;
+        wj = scored ? (p.variant == CAOTE_FAST ? 1.f : hj) : 0.f;
+        zsum += scored ? hj : 0.f;
       }
-      w_lds[tid] = scored ? (p.variant == CAOTE_FAST ? 1.f : hj) : 0.f;
-      zsum += scored ? hj : 0.f;
     }
-    __syncthreads();
-    // ---- phase B: stream the chunk of V -----------------------------------------------
+    // ---- the weighted sum over the wave's 64 value rows, kUnroll loads in flight -------------
 #pragma unroll
     for (int it0 = 0; it0 < ITER; it0 += kUnroll) {
-      Frag<T> f[kUnroll];
-      float w[kUnroll];
 #pragma unroll
       for (int u = 0; u < kUnroll; ++u) {
-        const int rl = (it0 + u) * RPI + team;
-        w[u] = w_lds[rl];
-        if (w[u] != 0.f) fetch(Vb + (int64_t)(c0 + rl) * p.vsn, f[u]); else zero(f[u]);
-      }
-#pragma unroll
-      for (int u = 0; u < kUnroll; ++u) {
+        const float w = __shfl(wj, (it0 + u) * RPW + sub, kWave);
         float x[8];
         widen(f[u], x);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = fmaf(w[u], x[e], acc[e]);
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(w, x[e], acc[e]);
+        if (it0 + kUnroll < ITER) {                          // the same slot, next group of rows
+          const int j = c0 + (it0 + kUnroll + u) * RPW + sub;
+          if (j < N) fetch(Vb + (int64_t)j * p.vsn, f[u]); else zero(f[u]);
+        }
       }
     }
-    __syncthreads();                        // w_lds is rewritten by the next chunk
+  }
+  // ---- the rows of a wave, then the waves ----------------------------------------------------
+#pragma unroll
+  for (int o = TL; o < kWave; o <<= 1) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
   }
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) zsum += __shfl_xor(zsum, o, kWave);
-  if ((tid & 63) == 0) zred[tid >> 6] = zsum;
+  if (lane < TL) {
 #pragma unroll
-  for (int e = 0; e < 8; ++e) red[team][tl * 8 + e] = acc[e];
+    for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = acc[e];
+  }
+  if (lane == 0) red[wave][D] = zsum;
   __syncthreads();
-  if (tid < D) {
+  if (tid <= D) {
     float s = 0.f;
 #pragma unroll
-    for (int t = 0; t < RPI; ++t) s += red[t][tid];
-    p.opart[((int64_t)bh * p.n_vpart + blockIdx.x) * D + tid] = s;
-  } else if (tid == D) {
-    float z = 0.f;
-#pragma unroll
-    for (int w = 0; w < kThreads / kWave; ++w) z += zred[w];
-    p.zpart[(int64_t)bh * p.n_vpart + blockIdx.x] = z;
+    for (int w = 0; w < NW; ++w) s += red[w][tid];
+    if (tid < D) p.opart[((int64_t)bh * p.n_vpart + blockIdx.x) * D + tid] = s;
+    else         p.zpart[(int64_t)bh * p.n_vpart + blockIdx.x] = s;
   }
 }
 
