@@ -49,6 +49,7 @@ struct Params {
   int32_t* sel_head;  // [BH][4]               threshold bin, rank inside it, its population
   int n_span;
   int hist_zeroed;    // an earlier kernel of this call has cleared `hist` (fused call)
+  int select_swaps;   // fused call on a short cache: the selection also does the evict-one row swap
   void* stage;        // compaction staging
   int n_split, split_len, Rp, n_vchunk, vchunk_len;
   int vrep, n_vsum;   // value sum: 256-token chunks per workgroup, partial sums per head
@@ -116,9 +117,11 @@ __device__ __forceinline__ void reset_counters(const Params& p, int bh) {
   for (int i = threadIdx.x; i < kHistBins; i += blockDim.x) p.hist[(int64_t)bh * kHistBins + i] = 0u;
 }
 
-// Order-preserving map float -> uint32 (larger float <=> larger key).
+// Order-preserving map float -> uint32 (larger float <=> larger key; -0 and +0 share a key,
+// as they compare equal).
 __device__ __forceinline__ uint32_t float_key(float f) {
   uint32_t u = __float_as_uint(f);
+  u = u == 0x80000000u ? 0u : u;
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 

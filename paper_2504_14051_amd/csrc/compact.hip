@@ -134,8 +134,10 @@ hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int64_t chunks = (int64_t)p.budget * (row_bytes / 16);
   const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads), p.B * p.Hkv);
   if (p.mode == CAOTE_COMPACT_SWAP_LAST) {
-    hipLaunchKernelGGL(k_swap_last, dim3(p.B * p.Hkv), dim3(kThreads), 0, s, p, row_bytes);
-    mark(hook, "compact_swap");
+    if (!p.select_swaps) {               // else the selection kernel has moved the row already
+      hipLaunchKernelGGL(k_swap_last, dim3(p.B * p.Hkv), dim3(kThreads), 0, s, p, row_bytes);
+      mark(hook, "compact_swap");
+    }
     // with equal lengths and exactly one token over budget every sequence is an evict-one
     if (p.seq_lens == nullptr && p.cap - p.budget == 1) return hipGetLastError();
   }

@@ -24,6 +24,7 @@ constexpr int kPer = kSelSpan / kT;       // tokens per thread in a span (8)
 constexpr int kRows = kSelSpan / kW / kWave;   // 64-token rows per wave (8)
 constexpr int kSmallCand = 128;           // candidate lists up to this length are ranked in LDS
 static_assert(kPer * kT == kSelSpan && kRows * kW * kWave == kSelSpan, "span geometry");
+static_assert(kHistShift == 20, "the one-workgroup selection splits the open bits 10 + 10");
 
 // Exclusive prefix sum of v over the 256 threads of the block, and the block total.
 __device__ __forceinline__ int block_excl_scan(int v, int* wave_tot, int& total) {
@@ -357,10 +358,185 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
   }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Caches of up to 4096 rows (decode at a 2k-4k budget, block-wise prefill): the whole selection
+// of a head in ONE workgroup of 1024 threads, four consecutive tokens per thread, everything
+// in registers and LDS.  Three dependent kernels cost about 5 us each at this size, whatever
+// they do; one costs about 6.  In a fused evict-one call in swap-last mode the workgroup also
+// moves the last row into the hole it has just chosen (it knows the hole).
+// ---------------------------------------------------------------------------------------------
+constexpr int kST = 1024;                 // threads
+constexpr int kSW = kST / kWave;          // waves
+constexpr int kSPer = 4;                  // tokens per thread
+constexpr int kSmallCap = kST * kSPer;    // 4096
+
+// Exclusive prefix sum over the 1024 threads, and the total.  wave_tot: kSW ints of LDS.
+__device__ __forceinline__ int block_excl_scan_1024(int v, int* wave_tot, int& total) {
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int up = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += up;
+  }
+  __syncthreads();                        // wave_tot is reused by consecutive calls
+  if (lane == kWave - 1) wave_tot[wv] = inc;
+  __syncthreads();
+  int before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kSW; ++w) {
+    const int t = wave_tot[w];
+    before += w < wv ? t : 0;
+    tot += t;
+  }
+  total = tot;
+  return before + inc - v;
+}
+
+__global__ __launch_bounds__(kST) void k_select_small(const Params p, int row_bytes) {
+  const int bh = blockIdx.x, b = bh / p.Hkv, hk = bh % p.Hkv;
+  const int N = seq_len(p, b);
+  const int k = p.budget;
+  const int tid = threadIdx.x;
+  int32_t* out = p.kept + (int64_t)bh * k;
+  if (N <= k) {                           // nothing to evict: identity, -1 padded
+    for (int i = tid; i < k; i += kST) out[i] = i < N ? i : -1;
+    return;
+  }
+  __shared__ int hist[kHistBins];
+  __shared__ uint32_t cand[kSmallCap];
+  __shared__ int wave_tot[kSW];
+  __shared__ uint32_t s_prefix;
+  __shared__ int s_bin, s_krem, s_hole;
+
+  const float* sc = p.scores + (int64_t)bh * p.cap;
+  const int j0 = tid * kSPer;             // this thread's tokens j0 .. j0+3
+  uint32_t key[kSPer];
+  bool valid[kSPer];
+#pragma unroll
+  for (int e = 0; e < kSPer; ++e) {
+    valid[e] = j0 + e < N;
+    key[e] = valid[e] ? float_key(sc[j0 + e]) : 0u;
+  }
+#pragma unroll
+  for (int u = 0; u < kHistBins / kST; ++u) hist[tid + u * kST] = 0;
+  if (tid == 0) s_hole = -1;
+  __syncthreads();
+#pragma unroll
+  for (int e = 0; e < kSPer; ++e)
+    if (valid[e]) atomicAdd(&hist[key[e] >> kHistShift], 1);
+  __syncthreads();
+  // ---- the bin that holds the k-th largest key: threads walk down from the largest bin ------
+  {
+    constexpr int BPT = kHistBins / kST;
+    const int top = kHistBins - 1 - tid * BPT;
+    int cnt[BPT], mine = 0;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) { cnt[i] = hist[top - i]; mine += cnt[i]; }
+    int total;
+    int above = block_excl_scan_1024(mine, wave_tot, total);
+    if (above < k && k <= above + mine) {  // exactly one thread
+#pragma unroll
+      for (int i = 0; i < BPT; ++i) {
+        if (above < k && k <= above + cnt[i]) { s_bin = top - i; s_krem = k - above; }
+        above += cnt[i];
+      }
+    }
+    __syncthreads();
+  }
+  const uint32_t bin = (uint32_t)s_bin;
+  int krem = s_krem;                      // rank still to locate inside the bin
+  // ---- the bin's keys, as a list in LDS -----------------------------------------------------------
+  int ncand;
+  {
+    int c = 0;
+#pragma unroll
+    for (int e = 0; e < kSPer; ++e) c += valid[e] && (key[e] >> kHistShift) == bin;
+    int at = block_excl_scan_1024(c, wave_tot, ncand);
+#pragma unroll
+    for (int e = 0; e < kSPer; ++e)
+      if (valid[e] && (key[e] >> kHistShift) == bin) cand[at++] = key[e];
+    __syncthreads();
+  }
+  // ---- radix search on the low 20 bits over the list, 10 bits a pass: one bin per thread ------
+  uint32_t prefix = bin << kHistShift;
+  int shift = kHistShift;
+  while (shift > 0) {
+    const int bits = shift >= 10 ? 10 : shift;
+    shift -= bits;
+    const uint32_t himask = 0xffffffffu << (shift + bits);
+    hist[tid] = 0;
+    __syncthreads();
+    for (int i = tid; i < ncand; i += kST) {
+      const uint32_t ck = cand[i];
+      if ((ck & himask) == prefix) atomicAdd(&hist[(ck >> shift) & ((1u << bits) - 1u)], 1);
+    }
+    __syncthreads();
+    {
+      const int nd = 1 << bits;
+      const int mine = tid < nd ? hist[nd - 1 - tid] : 0;
+      int total;
+      const int above = block_excl_scan_1024(mine, wave_tot, total);
+      if (tid < nd && above < krem && krem <= above + mine) {   // exactly one thread
+        s_prefix = prefix | ((uint32_t)(nd - 1 - tid) << shift);
+        s_krem = krem - above;
+      }
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    krem = s_krem;
+    __syncthreads();
+  }
+  const uint32_t theta = prefix;          // key of the k-th largest score; krem of its ties are kept
+  // ---- emit in ascending order: a token's rank = kept tokens before it ---------------------------
+  int gt = 0, eq = 0;
+#pragma unroll
+  for (int e = 0; e < kSPer; ++e) { gt += valid[e] && key[e] > theta; eq += valid[e] && key[e] == theta; }
+  int tot_gt, tot_eq;
+  const int gt_before = block_excl_scan_1024(gt, wave_tot, tot_gt);
+  const int eq_before = block_excl_scan_1024(eq, wave_tot, tot_eq);
+  int pos = gt_before + min(eq_before, krem);
+  int ties_left = max(0, krem - eq_before);
+  int dropped = -1;                       // a token of this thread that is not kept
+#pragma unroll
+  for (int e = 0; e < kSPer; ++e) {
+    bool keep = valid[e] && key[e] > theta;
+    if (valid[e] && key[e] == theta && ties_left > 0) { keep = true; --ties_left; }
+    if (keep) out[pos++] = j0 + e;
+    else if (valid[e]) dropped = j0 + e;
+  }
+  // ---- evict-one in swap-last mode (fused call): the last row drops into the hole ----------------
+  if (p.select_swaps && p.mode == CAOTE_COMPACT_SWAP_LAST && N - k == 1) {
+    if (dropped >= 0) s_hole = dropped;    // exactly one token of the head is dropped
+    __syncthreads();
+    const int hole = s_hole;
+    if (hole < 0 || hole == N - 1) return;
+    const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
+    char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
+    char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
+    const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
+    const int cpr = row_bytes / 16;
+    if (tid < cpr)
+      *reinterpret_cast<uint4*>(Kb + hole * krow + tid * 16) = *reinterpret_cast<const uint4*>(Kb + (N - 1) * krow + tid * 16);
+    else if (tid < 2 * cpr)
+      *reinterpret_cast<uint4*>(Vb + hole * vrow + (tid - cpr) * 16) =
+          *reinterpret_cast<const uint4*>(Vb + (N - 1) * vrow + (tid - cpr) * 16);
+    else if (tid == 2 * cpr && p.base)
+      p.base[(int64_t)bh * p.cap + hole] = p.base[(int64_t)bh * p.cap + N - 1];
+  }
+}
+
 }  // namespace
 
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int bh = p.B * p.Hkv;
+  if (p.cap <= kSmallCap) {
+    const int row_bytes = p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
+    hipLaunchKernelGGL(k_select_small, dim3(bh), dim3(kST), 0, s, p, row_bytes);
+    mark(hook, "select");
+    return hipGetLastError();
+  }
   if (!p.hist_zeroed) hipLaunchKernelGGL(k_select_zero, dim3(bh), dim3(kT), 0, s, p);
   hipLaunchKernelGGL(k_select_hist, dim3((p.cap + 4095) / 4096, bh), dim3(1024), 0, s, p);
   mark(hook, "select_hist");

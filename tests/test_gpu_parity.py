@@ -330,8 +330,9 @@ def _layout_only(B, batch, hkv, cap, d=128, dtype=torch.bfloat16):
     return B.make_layout(q, K, K, base=B.BASE_NONE, softmax_scale=1.0), K
 
 
-@pytest.mark.parametrize("cap,budget", [(1, 1), (63, 10), (1000, 999), (5000, 1234), (40000, 2048),
-                                        (131072, 4096), (300000, 100000)])
+@pytest.mark.parametrize("cap,budget", [(1, 1), (63, 10), (1000, 999), (2049, 2048), (4096, 100), (4096, 4095),
+                                        (4097, 2048), (5000, 1234), (40000, 2048), (131072, 4096),
+                                        (300000, 100000)])
 def test_select_exact_with_ties_and_infinities(B, oracle, cap, budget):
     rng = np.random.default_rng(cap)
     sc = rng.standard_normal((2, 3, cap)).astype(np.float32)
