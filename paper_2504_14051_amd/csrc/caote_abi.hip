@@ -277,7 +277,7 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
   // the merge of the row statistics (or, on the matrix-core path, the second sweep) clears
   // the selection's counters on its way
   p.hist_zeroed = (!p.lse_in || p.use_mfma) ? 1 : 0;
-  p.select_swaps = p.cap <= 4096 ? 1 : 0;   // (the one-workgroup selection of launch_select)
+  p.select_swaps = p.cap <= 16384 ? 1 : 0;  // (the one-workgroup selections of launch_select)
   if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
   st = do_score(p, s, hook);
   if (st != CAOTE_OK) return st;
