@@ -277,6 +277,9 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
   // the merge of the row statistics (or, on the matrix-core path, the second sweep) clears
   // the selection's counters on its way
   p.hist_zeroed = (!p.lse_in || p.use_mfma) ? 1 : 0;
+  // up to 128 scoring workgroups per head add to the same few dozen bins: beyond that the
+  // serialised device atomics outlast the kernel, and a histogram kernel of its own is faster
+  p.hist_in_vscore = (p.cap > 16384 && p.cap <= 32768 && p.hist_zeroed) ? 1 : 0;
   p.select_swaps = p.cap <= 16384 ? 1 : 0;  // (the one-workgroup selections of launch_select)
   if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
   st = do_score(p, s, hook);

@@ -49,6 +49,7 @@ struct Params {
   int32_t* sel_head;  // [BH][4]               threshold bin, rank inside it, its population
   int n_span;
   int hist_zeroed;    // an earlier kernel of this call has cleared `hist` (fused call)
+  int hist_in_vscore; // fused call, long cache: k_vscore builds the selection's histogram
   int select_swaps;   // fused call on a short cache: the selection also does the evict-one row swap
   void* stage;        // compaction staging
   int n_split, split_len, Rp, n_vchunk, vchunk_len;

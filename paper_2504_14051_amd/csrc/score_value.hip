@@ -290,6 +290,11 @@ __global__ __launch_bounds__(kThreads) void k_vscore(const Params p) {
   const int n_scored = hi - lo;
 
   __shared__ float d_lds[kVChunk];        // ||v_j - o|| of each row of the chunk
+  __shared__ uint32_t lh[kHistBins];      // hist_in_vscore: this chunk's histogram of score keys
+  if (p.hist_in_vscore) {
+#pragma unroll
+    for (int u = 0; u < kHistBins / kThreads; ++u) lh[threadIdx.x + u * kThreads] = 0u;
+  }
 
   const float* os = p.osum + (int64_t)bh * (kMaxD + 1);
   const float Z = os[kMaxD];
@@ -322,13 +327,27 @@ __global__ __launch_bounds__(kThreads) void k_vscore(const Params p) {
   __syncthreads();
   // ---- one thread per token: the score ------------------------------------------------------
   const int j = c0 + tid;
-  if (j >= N) return;
   float out = INFINITY;
-  if (j >= lo && j < hi && n_scored > 1) {
-    const float hj = p.h[(int64_t)bh * p.cap + j];
-    out = Z > 0.f ? hj / fmaxf(Z - hj, FLT_MIN) * d_lds[tid] : 0.f;
+  if (j < N) {
+    if (j >= lo && j < hi && n_scored > 1) {
+      const float hj = p.h[(int64_t)bh * p.cap + j];
+      out = Z > 0.f ? hj / fmaxf(Z - hj, FLT_MIN) * d_lds[tid] : 0.f;
+    }
+    p.scores[(int64_t)bh * p.cap + j] = out;
   }
-  p.scores[(int64_t)bh * p.cap + j] = out;
+  // ---- fused call, long cache: the selection's 4096-bin histogram of the score keys, added up
+  // per workgroup in LDS first (the scores of a head crowd into a few dozen bins, and
+  // same-address device atomics serialise), then one global atomic per touched bin ----------
+  if (p.hist_in_vscore) {
+    if (j < N) atomicAdd(&lh[float_key(out) >> kHistShift], 1u);
+    __syncthreads();
+    uint32_t* gh = p.hist + (int64_t)bh * kHistBins;
+#pragma unroll
+    for (int u = 0; u < kHistBins / kThreads; ++u) {
+      const uint32_t c = lh[tid + u * kThreads];
+      if (c) atomicAdd(&gh[tid + u * kThreads], c);
+    }
+  }
 }
 
 template <typename T, int D>

@@ -695,8 +695,10 @@ hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook) {
     return hipGetLastError();
   }
   if (!p.hist_zeroed) hipLaunchKernelGGL(k_select_zero, dim3(bh), dim3(kT), 0, s, p);
-  hipLaunchKernelGGL(k_select_hist, dim3((p.cap + 4095) / 4096, bh), dim3(1024), 0, s, p);
-  mark(hook, "select_hist");
+  if (!p.hist_in_vscore) {               // else the scoring kernel has built the histogram
+    hipLaunchKernelGGL(k_select_hist, dim3((p.cap + 4095) / 4096, bh), dim3(1024), 0, s, p);
+    mark(hook, "select_hist");
+  }
   hipLaunchKernelGGL(k_select_span, dim3(p.n_span, bh), dim3(kT), 0, s, p);
   mark(hook, "select_span");
   const int n_out = (max(p.cap, p.budget) + kSelSpan - 1) / kSelSpan;   // also pads past the cache
