@@ -254,6 +254,34 @@ def test_snapkv_pool_widths(B, oracle, pool, window):
     full_check(B, oracle, synth.make_cache(wl, seq_lens=lens), wl.budget)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_layouts(B, oracle, seed):
+    """Seeded random shapes across every key-sweep variant, base mode, dtype, window mode,
+    budget and ragged lengths: whatever path the planner picks has to match the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    hkv = int(rng.choice([1, 2, 4]))
+    G = int(rng.choice([1, 2, 4, 7]))
+    d = int(rng.choice([64, 128]))
+    dtype = "f32" if rng.random() < 0.25 else "bf16"
+    W = int(rng.choice([1, 2, 5, 16, 33, 64]))
+    batch = int(rng.integers(1, 4))
+    context = int(rng.integers(W + 2, 3000))
+    budget = int(rng.integers(1, context))
+    base = int(rng.choice([synth.BASE_NONE, synth.BASE_H2O, synth.BASE_SNAPKV]))
+    pool = int(rng.choice([1, 3, 7, 15])) if base == synth.BASE_SNAPKV else 1
+    wic = int(rng.random() < 0.7)
+    tail = int(rng.choice([0, 0, W, 3]))
+    head = int(rng.choice([0, 0, 1, 4]))
+    wl = synth.Workload(f"rand{seed}", batch, hkv * G, hkv, d, dtype, context, W, budget, base,
+                        pool_kernel=pool, n_protect_head=head, n_protect_tail=tail,
+                        window_in_cache=wic, seed=4242 + seed)
+    lens = rng.integers(W + 1, context + 1, size=batch).astype(np.int32)
+    lens[0] = context
+    cache = synth.make_cache(wl, seq_lens=lens, base_init="random")
+    mode = int(rng.random() < 0.3)
+    full_check(B, oracle, cache, budget, mode=mode, variant=int(rng.random() < 0.3))
+
+
 def test_fastcaote_variant(B, oracle):
     wl = small(base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=8)
     full_check(B, oracle, synth.make_cache(wl), wl.budget, variant=1)
