@@ -76,6 +76,8 @@ def lib():
         L.oracle_bruteforce_delete_token.restype = None
         L.oracle_joint_eviction_error.argtypes = [_dp, _dp, i, i, _ip, i]
         L.oracle_joint_eviction_error.restype = dbl
+        L.oracle_greedy_joint_evict.argtypes = [_dp, _dp, i, i, i, i, i, _ip, _dp]
+        L.oracle_greedy_joint_evict.restype = i
         _lib = L
     return _lib
 
@@ -232,6 +234,23 @@ def joint_eviction_error(w, v, token_set):
     N, d = v.shape
     s = np.ascontiguousarray(token_set, dtype=np.int32)
     return lib().oracle_joint_eviction_error(wp, vp, N, d, s.ctypes.data_as(_ip), s.shape[0])
+
+
+def greedy_joint_evict(w, v, m, lo=0, hi=None):
+    """Greedy eviction of m tokens by the joint error.  w [N] (sums to 1 over [lo,hi)),
+    v [N, d] -> (order [m] int32, err [m]): the token evicted at each step and the joint
+    error of everything evicted up to and including it."""
+    w, wp = _d(w)
+    v, vp = _d(v)
+    N, d = v.shape
+    hi = N if hi is None else hi
+    order = np.empty(m, dtype=np.int32)
+    err = np.empty(m, dtype=np.float64)
+    rc = lib().oracle_greedy_joint_evict(wp, vp, N, d, lo, hi, m, order.ctypes.data_as(_ip),
+                                         err.ctypes.data_as(_dp))
+    if rc != 0:
+        raise ValueError("oracle_greedy_joint_evict: bad arguments")
+    return order, err
 
 
 # ---- batched loops over (sequence, KV head) ----------------------------------

@@ -301,6 +301,94 @@ def test_joint_score_reduces_to_single_and_matches_two_token_removal(oracle):
         assert np.isclose(oracle.joint_eviction_error(w, v, [i, j]), np.linalg.norm(o - o2), rtol=1e-11)
 
 
+def _removal_error(w, v, gone):
+    """Joint error by its definition: take the tokens out, renormalise, measure the change."""
+    keep = np.ones(len(w), bool)
+    keep[list(gone)] = False
+    if not keep.any() or w[keep].sum() <= 0:
+        return np.inf
+    return np.linalg.norm(w @ v - (w[keep] / w[keep].sum()) @ v[keep])
+
+
+def test_joint_error_matches_removal_of_larger_sets(oracle):
+    n, d = 9, 5
+    w = _weights(n)
+    v = RNG.standard_normal((n, d))
+    for m in (3, 4, 6):
+        for gone in itertools.islice(itertools.combinations(range(n), m), 12):
+            assert np.isclose(oracle.joint_eviction_error(w, v, list(gone)), _removal_error(w, v, gone),
+                              rtol=1e-10)
+
+
+def test_greedy_joint_eviction_step_by_step_against_real_removal(oracle):
+    """Every step of the greedy evicts the candidate whose real removal, together with what
+    is already gone, changes the output least (App. B), and reports that change."""
+    n, d, m = 12, 4, 7
+    for trial in range(4):
+        w = _weights(n)
+        v = RNG.standard_normal((n, d)) * np.exp(RNG.standard_normal((n, 1)))
+        order, err = oracle.greedy_joint_evict(w, v, m)
+        assert len(set(order.tolist())) == m
+        gone = []
+        for t in range(m):
+            cand = {j: _removal_error(w, v, gone + [j]) for j in range(n) if j not in gone}
+            best = min(cand.values())
+            assert np.isclose(cand[int(order[t])], best, rtol=1e-10), (trial, t)
+            assert np.isclose(err[t], best, rtol=1e-9)
+            gone.append(int(order[t]))
+        # and the reported errors are the general m-token formula on the evicted prefix
+        for t in range(m):
+            assert np.isclose(err[t], oracle.joint_eviction_error(w, v, order[:t + 1]), rtol=1e-10)
+
+
+def test_greedy_joint_first_step_is_the_single_token_choice(oracle):
+    n, d = 40, 8
+    w = _weights(n)
+    v = RNG.standard_normal((n, d))
+    c, _, _ = oracle.caote_scores(w, v)
+    order, err = oracle.greedy_joint_evict(w, v, 1)
+    assert order[0] == np.argmin(c) and np.isclose(err[0], c.min(), rtol=1e-12)
+
+
+def test_greedy_joint_finds_a_cancelling_pair(oracle):
+    """Two tokens whose weighted offsets from the output are opposite cancel exactly: after
+    one of them is gone the other is the next to go and the joint error drops to zero,
+    although a third token has a smaller single-token score than the second."""
+    n, d = 8, 6
+    w = _weights(n)
+    v = RNG.standard_normal((n, d))
+    x = np.zeros(d)
+    x[0] = 1e-3                                          # tiny offset: token 0 goes first
+    # tokens 0 and 1: w0 (o - v0) = -w1 (o - v1) = -x; the others are re-centred so that o = 0
+    rest = np.arange(2, n)
+    v[rest] -= (w[rest] @ v[rest]) / w[rest].sum()
+    v[0] = x / w[0]
+    v[1] = -x / w[1]
+    assert np.allclose(w @ v, 0, atol=1e-15)
+    c, _, _ = oracle.caote_scores(w, v)
+    assert np.argmin(c) in (0, 1)
+    order, err = oracle.greedy_joint_evict(w, v, 2)
+    assert set(order.tolist()) == {0, 1}
+    assert err[1] < 1e-12 and err[0] > 1e-4
+
+
+def test_greedy_joint_protected_rows_ties_and_exhaustion(oracle):
+    n, d = 10, 3
+    v = RNG.standard_normal((n, d))
+    h = RNG.random(n)
+    _, w, _ = oracle.caote_scores(h, v, lo=2, hi=8)
+    order, _ = oracle.greedy_joint_evict(w, v, 6, lo=2, hi=8)      # every scored token goes
+    assert sorted(order.tolist()) == list(range(2, 8))
+    # identical tokens tie: the higher index leaves first
+    v2 = np.tile(RNG.standard_normal((1, d)), (n, 1))
+    v2[0] += 1.0
+    w2 = np.full(n, 1.0 / n)
+    order, _ = oracle.greedy_joint_evict(w2, v2, 3)
+    assert order.tolist() == [9, 8, 7]
+    with pytest.raises(ValueError):
+        oracle.greedy_joint_evict(w, v, 7, lo=2, hi=8)
+
+
 # ---- selection and compaction -----------------------------------------------------
 
 def test_select_against_lexsort(oracle):
