@@ -76,6 +76,8 @@ def lib():
         L.oracle_bruteforce_delete_token.restype = None
         L.oracle_joint_eviction_error.argtypes = [_dp, _dp, i, i, _ip, i]
         L.oracle_joint_eviction_error.restype = dbl
+        L.oracle_joint_candidates.argtypes = [_dp, _dp, i, i, i, i, _ip, i, _dp]
+        L.oracle_joint_candidates.restype = None
         L.oracle_greedy_joint_evict.argtypes = [_dp, _dp, i, i, i, i, i, _ip, _dp]
         L.oracle_greedy_joint_evict.restype = i
         _lib = L
@@ -234,6 +236,20 @@ def joint_eviction_error(w, v, token_set):
     N, d = v.shape
     s = np.ascontiguousarray(token_set, dtype=np.int32)
     return lib().oracle_joint_eviction_error(wp, vp, N, d, s.ctypes.data_as(_ip), s.shape[0])
+
+
+def joint_candidates(w, v, gone, lo=0, hi=None):
+    """Joint error of evicting token j on top of the tokens in `gone`, for every scored j
+    not in `gone`; NaN elsewhere.  w [N] (sums to 1 over [lo,hi)), v [N, d] -> c [N]."""
+    w, wp = _d(w)
+    v, vp = _d(v)
+    N, d = v.shape
+    hi = N if hi is None else hi
+    s = np.ascontiguousarray(gone, dtype=np.int32)
+    c = np.empty(N, dtype=np.float64)
+    lib().oracle_joint_candidates(wp, vp, N, d, lo, hi, s.ctypes.data_as(_ip), s.shape[0],
+                                  c.ctypes.data_as(_dp))
+    return c
 
 
 def greedy_joint_evict(w, v, m, lo=0, hi=None):

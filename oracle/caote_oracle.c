@@ -438,51 +438,67 @@ double oracle_joint_eviction_error(const double *w, const double *v, int N,
 }
 
 /* ------------------------------------------------------------------------- *
- * Greedy multi-token eviction under the joint error (App. "Extending CAOTE
- * to Multi-token Eviction"; the appendix notes that the exact choice among all
- * token sets is combinatorial and leaves greedy strategies as the way out).
- * Tokens leave one at a time.  With S the set evicted so far, a step evicts
- * the scored token j outside S whose joint error with S is smallest:
- *     c_{S+j} = || u + w_j (o - v_j) ||_2 / (1 - a - w_j),
- *     u = sum_{i in S} w_i (o - v_i),   a = sum_{i in S} w_i,
- * where o = sum_i w_i v_i is the output BEFORE any eviction (the general
- * m-token formula of the appendix, evaluated for S + j).  A candidate that
- * would leave no weight behind (1 - a - w_j <= 0) has error +INF.  Equal
- * errors evict the higher index (the lower one is kept, as in oracle_select).
+ * One step of multi-token eviction (App. "Extending CAOTE to Multi-token
+ * Eviction"): with the set S = set[0..m) already evicted, the joint error of
+ * evicting scored token j as well, by the appendix's m-token formula applied to
+ * S + j:
+ *     c_{S+j} = || sum_{i in S+j} w_i (o - v_i) ||_2 / (1 - sum_{i in S+j} w_i),
+ * o = sum_i w_i v_i being the output BEFORE any eviction.  A candidate that
+ * would leave no weight behind (denominator <= 0) has error +INF.
  *   w [N] sums to 1 over the scored rows [lo,hi) (entries outside are ignored),
- *   v [N][d], m <= hi - lo evictions
- *   -> order [m]: the evicted token of each step;  err [m]: c_S after it.
- * Returns 0, or -1 on bad arguments.
+ *   v [N][d]  ->  c [N]; NaN for rows that are not candidates (in S, or outside
+ *   [lo,hi)).
  * ------------------------------------------------------------------------- */
+void oracle_joint_candidates(const double *w, const double *v, int N, int d,
+                             int lo, int hi, const int32_t *set, int m, double *c)
+{
+    double *o = (double *)calloc((size_t)d, sizeof(double));
+    double *u = (double *)calloc((size_t)d, sizeof(double));
+    double a = 0.0;
+    for (int i = lo; i < hi; ++i)
+        for (int x = 0; x < d; ++x) o[x] += w[i] * v[(size_t)i * d + x];
+    for (int j = 0; j < N; ++j) c[j] = (j >= lo && j < hi) ? 0.0 : NAN;
+    for (int t = 0; t < m; ++t) {
+        int i = set[t];
+        a += w[i];
+        for (int x = 0; x < d; ++x) u[x] += w[i] * (o[x] - v[(size_t)i * d + x]);
+        c[i] = NAN;
+    }
+    for (int j = lo; j < hi; ++j) {
+        if (isnan(c[j])) continue;
+        double rest = 1.0 - a - w[j], n2 = 0.0;
+        for (int x = 0; x < d; ++x) {
+            double y = u[x] + w[j] * (o[x] - v[(size_t)j * d + x]);
+            n2 += y * y;
+        }
+        c[j] = rest > 0.0 ? sqrt(n2) / rest : INFINITY;
+    }
+    free(o); free(u);
+}
+
+/* Greedy multi-token eviction under the joint error (the appendix notes that
+ * the exact choice among all token sets is combinatorial and leaves greedy
+ * strategies as the way out).  Tokens leave one at a time: each step evicts the
+ * candidate with the smallest joint error given what is already gone; equal
+ * errors evict the higher index (the lower one is kept, as in oracle_select).
+ *   m <= hi - lo evictions -> order [m]: the evicted token of each step;
+ *   err [m]: the joint error of everything evicted up to and including it.
+ * Returns 0, or -1 on bad arguments.                                         */
 int oracle_greedy_joint_evict(const double *w, const double *v, int N, int d,
                               int lo, int hi, int m, int32_t *order, double *err)
 {
     if (lo < 0 || hi > N || lo > hi || m < 0 || m > hi - lo) return -1;
-    double *o = (double *)calloc((size_t)d, sizeof(double));
-    double *u = (double *)calloc((size_t)d, sizeof(double));
-    unsigned char *gone = (unsigned char *)calloc((size_t)(N > 0 ? N : 1), 1);
-    double a = 0.0;
-    for (int i = lo; i < hi; ++i)
-        for (int x = 0; x < d; ++x) o[x] += w[i] * v[(size_t)i * d + x];
+    double *c = (double *)malloc((size_t)(N > 0 ? N : 1) * sizeof(double));
     for (int t = 0; t < m; ++t) {
         int best = -1;
-        double best_c = INFINITY;
+        oracle_joint_candidates(w, v, N, d, lo, hi, order, t, c);
         for (int j = lo; j < hi; ++j) {
-            if (gone[j]) continue;
-            double rest = 1.0 - a - w[j], n2 = 0.0, c;
-            for (int x = 0; x < d; ++x) {
-                double y = u[x] + w[j] * (o[x] - v[(size_t)j * d + x]);
-                n2 += y * y;
-            }
-            c = rest > 0.0 ? sqrt(n2) / rest : INFINITY;
-            if (best < 0 || c < best_c || (c == best_c && j > best)) { best = j; best_c = c; }
+            if (isnan(c[j])) continue;
+            if (best < 0 || c[j] < c[best] || (c[j] == c[best] && j > best)) best = j;
         }
-        gone[best] = 1;
-        a += w[best];
-        for (int x = 0; x < d; ++x) u[x] += w[best] * (o[x] - v[(size_t)best * d + x]);
         order[t] = best;
-        err[t] = best_c;
+        err[t] = c[best];
     }
-    free(o); free(u); free(gone);
+    free(c);
     return 0;
 }

@@ -339,6 +339,12 @@ def test_greedy_joint_eviction_step_by_step_against_real_removal(oracle):
         # and the reported errors are the general m-token formula on the evicted prefix
         for t in range(m):
             assert np.isclose(err[t], oracle.joint_eviction_error(w, v, order[:t + 1]), rtol=1e-10)
+        # the per-step candidate table: the m-token formula for S + j, NaN for what is gone
+        c = oracle.joint_candidates(w, v, order[:3])
+        assert np.isnan(c[order[:3]]).all()
+        for j in range(n):
+            if j not in order[:3]:
+                assert np.isclose(c[j], _removal_error(w, v, list(order[:3]) + [j]), rtol=1e-10)
 
 
 def test_greedy_joint_first_step_is_the_single_token_choice(oracle):
