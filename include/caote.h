@@ -170,6 +170,31 @@ caote_status caote_evict(const void* q_window, void* K, void* V, float* base_sco
                          float* scores, int32_t* kept_idx, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
 
+/* Greedy multi-token eviction (App. "Extending CAOTE to Multi-token Eviction"): the
+ * fused call with the selection taken under the JOINT error instead of the independent
+ * single-token scores.  With w, o and v as in caote_score, the error of evicting a set S is
+ *   c_S = || sum_{i in S} w_i (o - v_i) ||_2 / (1 - sum_{i in S} w_i);
+ * the exact minimiser over all sets is combinatorial, so tokens leave one at a time: each of
+ * the N_b - budget steps evicts the scored row j, not yet evicted, with the smallest
+ * c_{S + j}; equal errors evict the higher index; a row whose eviction would leave no weight
+ * behind has error +INF.  The steps of one (sequence, KV head) run in sequence inside one
+ * workgroup: the time grows with (N_b - budget) * N_b, which is why the call is limited to
+ * capacity <= CAOTE_JOINT_MAX_CAPACITY and meant for block-wise prefill and generation, where
+ * few tokens leave per call.  Only CAOTE_EXACT; budget >= n_protect_head + n_protect_tail.
+ *   scores       out, the single-token scores as caote_score writes them
+ *   kept_idx     out, as caote_select: ascending, -1 padded
+ *   evicted      DEVICE out int32 [batch][n_kv_heads][capacity - budget]: the row evicted at
+ *                each step, in eviction order, then -1
+ *   joint_error  DEVICE out fp32, same shape: c_S after each step, then NaN
+ * (both may be NULL when capacity == budget).  K, V and base_score are compacted as by
+ * caote_evict.  NaN weights or values are not allowed.                                */
+#define CAOTE_JOINT_MAX_CAPACITY 8192
+caote_status caote_evict_joint(const void* q_window, void* K, void* V, float* base_score,
+                               const caote_layout* layout, int32_t budget, int32_t mode,
+                               float* scores, int32_t* kept_idx, int32_t* evicted,
+                               float* joint_error, void* workspace, size_t workspace_bytes,
+                               void* hip_stream);
+
 /* Measurement aid (benchmarks, profiling): caote_evict with a HIP event recorded
  * on `hip_stream` between its kernels.  Unlike every other entry point it creates
  * and destroys HIP events and WAITS for the stream before returning.

@@ -22,7 +22,7 @@ EXACT, FAST = 0, 1
 COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
 
 EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
-           "caote_append", "caote_evict", "caote_evict_timed", "caote_phase_name", "caote_last_error",
+           "caote_append", "caote_evict", "caote_evict_joint", "caote_evict_timed", "caote_phase_name", "caote_last_error",
            "caote_version")
 MAX_PHASES = 16
 
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.caote_append.restype = ctypes.c_int
         L.caote_evict.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp]
         L.caote_evict.restype = ctypes.c_int
+        L.caote_evict_joint.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.caote_evict_joint.restype = ctypes.c_int
         L.caote_evict_timed.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp,
                                         ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         L.caote_evict_timed.restype = ctypes.c_int
@@ -181,6 +183,15 @@ def caote_evict(q_window, K, V, base_score, layout: Layout, budget: int, mode, s
     _check(lib().caote_evict(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
                              ctypes.byref(layout), budget, mode, _ptr(scores), _ptr(kept_idx),
                              _ptr(workspace), wb, _stream(stream)))
+
+
+def caote_evict_joint(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores, kept_idx,
+                      evicted, joint_error, workspace, stream=None, workspace_bytes=None) -> None:
+    wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    _check(lib().caote_evict_joint(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
+                                   ctypes.byref(layout), budget, mode, _ptr(scores), _ptr(kept_idx),
+                                   _ptr(evicted), _ptr(joint_error), _ptr(workspace), wb,
+                                   _stream(stream)))
 
 
 def caote_evict_timed(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores,

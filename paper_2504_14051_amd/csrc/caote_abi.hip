@@ -184,7 +184,7 @@ extern "C" {
 
 const char* caote_last_error(void) { return g_err; }
 
-int32_t caote_version(void) { return 101; }
+int32_t caote_version(void) { return 102; }
 
 size_t caote_workspace_bytes(const caote_layout* layout, int32_t budget) {
   if (check_layout(layout, budget, false) != CAOTE_OK) return 0;
@@ -257,12 +257,26 @@ caote_status caote_append(void* K, void* V, float* base_score, const void* k_new
                        "append");
 }
 
+// `joint`: selection by the greedy joint error (evicted / joint_error are its extra outputs).
 static caote_status evict_impl(const void* q_window, void* K, void* V, float* base_score,
                                const caote_layout* layout, int32_t budget, int32_t mode,
                                float* scores, int32_t* kept_idx, void* workspace,
-                               size_t workspace_bytes, hipStream_t s, caote::PhaseHook* hook) {
+                               size_t workspace_bytes, hipStream_t s, caote::PhaseHook* hook,
+                               bool joint = false, int32_t* evicted = nullptr,
+                               float* joint_error = nullptr) {
   caote_status st = check_layout(layout, budget, true);
   if (st != CAOTE_OK) return st;
+  if (joint) {
+    if (layout->capacity > caote::kJointMaxCap)
+      return fail(CAOTE_EUNSUPPORTED, "greedy joint eviction supports a capacity of at most %d rows (got %d)",
+                  caote::kJointMaxCap, layout->capacity);
+    if (layout->variant != CAOTE_EXACT)
+      return fail(CAOTE_EUNSUPPORTED, "greedy joint eviction is defined for CAOTE_EXACT only");
+    if ((int64_t)layout->n_protect_head + layout->n_protect_tail > budget)
+      return fail(CAOTE_EINVAL, "budget (%d) is smaller than the number of protected rows", budget);
+    if (layout->capacity > budget && (!evicted || !joint_error))
+      return fail(CAOTE_EINVAL, "evicted and joint_error must not be NULL when capacity > budget");
+  }
   if (!q_window || !K || !V || !scores || !kept_idx)
     return fail(CAOTE_EINVAL, "q_window, K, V, scores and kept_idx must not be NULL");
   if (layout->base == CAOTE_BASE_H2O && !base_score)
@@ -281,10 +295,16 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
   // serialised device atomics outlast the kernel, and a histogram kernel of its own is faster
   p.hist_in_vscore = (p.cap > 16384 && p.cap <= 32768 && p.hist_zeroed) ? 1 : 0;
   p.select_swaps = p.cap <= 16384 ? 1 : 0;  // (the one-workgroup selections of launch_select)
+  if (joint) p.hist_in_vscore = p.select_swaps = 0;
   if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
   st = do_score(p, s, hook);
   if (st != CAOTE_OK) return st;
-  st = device_status(caote::launch_select(p, s, hook), "select");
+  if (joint) {
+    const int max_evict = p.cap > budget ? p.cap - budget : 0;
+    st = device_status(caote::launch_select_joint(p, evicted, joint_error, max_evict, s, hook), "select (joint)");
+  } else {
+    st = device_status(caote::launch_select(p, s, hook), "select");
+  }
   if (st != CAOTE_OK) return st;
   return device_status(caote::launch_compact(p, s, hook), "compact");
 }
@@ -295,6 +315,15 @@ caote_status caote_evict(const void* q_window, void* K, void* V, float* base_sco
                          void* hip_stream) {
   return evict_impl(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx, workspace,
                     workspace_bytes, (hipStream_t)hip_stream, nullptr);
+}
+
+caote_status caote_evict_joint(const void* q_window, void* K, void* V, float* base_score,
+                               const caote_layout* layout, int32_t budget, int32_t mode,
+                               float* scores, int32_t* kept_idx, int32_t* evicted,
+                               float* joint_error, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+  return evict_impl(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx, workspace,
+                    workspace_bytes, (hipStream_t)hip_stream, nullptr, true, evicted, joint_error);
 }
 
 caote_status caote_evict_timed(const void* q_window, void* K, void* V, float* base_score,

@@ -15,6 +15,7 @@ constexpr int kHistBins = 4096;   // selection histogram: top 12 bits of the sco
 constexpr int kHistShift = 20;
 constexpr int kSelSpan = 2048;    // tokens per workgroup in the selection kernels
 constexpr int kMaxSpans = 1024;   // spans per head the selection supports (2M tokens)
+constexpr int kJointMaxCap = CAOTE_JOINT_MAX_CAPACITY;   // greedy joint eviction: weights of a head fit LDS
 
 // Everything a kernel needs to know about one call.  Passed by value.
 struct Params {
@@ -142,6 +143,8 @@ hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_select_joint(const Params& p, int32_t* order, float* err, int max_evict, hipStream_t s,
+                               PhaseHook* hook);
 hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_append(const Params& p, const void* k_new, const void* v_new, int n_at, int n_new,
                          hipStream_t s);

@@ -10,6 +10,9 @@ from paper_2504_14051_amd import synth
 pytestmark = pytest.mark.gpu
 
 
+CAP_JOINT = 8192      # CAOTE_JOINT_MAX_CAPACITY
+
+
 @pytest.fixture(scope="module")
 def B():
     from paper_2504_14051_amd import binding
@@ -280,6 +283,108 @@ def test_random_layouts(B, oracle, seed):
     cache = synth.make_cache(wl, seq_lens=lens, base_init="random")
     mode = int(rng.random() < 0.3)
     full_check(B, oracle, cache, budget, mode=mode, variant=int(rng.random() < 0.3))
+
+
+def joint_check(B, oracle, cache, budget, mode=0):
+    """caote_evict_joint against the oracle's greedy (App. B).  A greedy choice is an argmin
+    over floats and one different choice changes every later step, so the GPU's sequence is
+    replayed: at step t, with the GPU's own first t evictions as S, the oracle's table of
+    c_{S+j} says how good the GPU's next choice was.  It has to be the oracle's best within
+    the rounding of the two candidates, |c| error <= 2 rtol (||u|| + w_j ||o - v_j||) / rest
+    (the terms of the sum before they cancel); the reported error has the same bound."""
+    wl = cache.wl
+    rtol = H.RTOL[wl.dtype]
+    ref = run_path(B, cache, budget, mode)              # scores and the state before compaction
+    dev = H.to_device(cache)
+    L = B.layout_for(wl, dev)
+    ws = torch.empty(B.caote_workspace_bytes(L, budget), dtype=torch.uint8, device="cuda")
+    Bn, Hkv, cap = dev.K.shape[:3]
+    n_ev = cap - budget
+    scores = torch.full((Bn, Hkv, cap), float("nan"), device="cuda")
+    kept = torch.full((Bn, Hkv, budget), -7, dtype=torch.int32, device="cuda")
+    evicted = torch.full((Bn, Hkv, n_ev), -7, dtype=torch.int32, device="cuda")
+    jerr = torch.full((Bn, Hkv, n_ev), -7.0, device="cuda")
+    base = dev.base if wl.base == synth.BASE_H2O else None
+    B.caote_evict_joint(dev.q, dev.K, dev.V, base, L, budget, mode, scores, kept, evicted, jerr, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(scores.cpu().numpy(), ref["scores"], equal_nan=True)
+    kept, evicted, jerr = kept.cpu().numpy(), evicted.cpu().numpy(), jerr.cpu().numpy()
+    _, oh, _ = H.oracle_scores(oracle, cache)
+    V = cache.V.double().numpy()
+    n_same = n_steps = 0
+    for b, N in enumerate(H.lengths(cache)):
+        lo = min(wl.n_protect_head, N)
+        hi = max(lo, N - wl.n_protect_tail)
+        m = min(N - min(N, budget), hi - lo)
+        for hk in range(Hkv):
+            v = V[b, hk, :N]
+            _, w, o = oracle.caote_scores(oh[b, hk, :N], v, lo, hi)
+            order = evicted[b, hk]
+            assert (order[m:] == -1).all() and np.isnan(jerr[b, hk, m:]).all()
+            assert len(set(order[:m].tolist())) == m and ((order[:m] >= lo) & (order[:m] < hi)).all()
+            gnorm = w * np.linalg.norm(o - v, axis=1)
+            u = np.zeros_like(o)
+            rest_all = 1.0
+            for t in range(m):
+                c = oracle.joint_candidates(w, v, order[:t], lo, hi)
+                s = int(order[t])
+                j_best = int(np.nanargmin(c))
+                scale = (np.linalg.norm(u) + gnorm) / np.maximum(rest_all - w, 1e-300)
+                slack = 2 * rtol * (scale[s] + scale[j_best])
+                if np.isfinite(c[j_best]):
+                    assert c[s] <= c[j_best] + slack, (b, hk, t, s, j_best, c[s], c[j_best])
+                    if rest_all - w[s] > 1e-3:
+                        assert abs(jerr[b, hk, t] - c[s]) <= 2 * rtol * scale[s] + 1e-30, (b, hk, t)
+                n_same += s == j_best
+                n_steps += 1
+                u += w[s] * (o - v[s])
+                rest_all -= w[s]
+            want = np.setdiff1d(np.arange(N), order[:m])
+            n_keep = min(N, budget)
+            assert np.array_equal(kept[b, hk, :n_keep], want) and (kept[b, hk, n_keep:] == -1).all()
+    H.check_compaction(oracle, ref["K_before"], ref["V_before"], ref["base_before"], dev.K.cpu(), dev.V.cpu(),
+                       None if base is None else base.cpu(), kept, cache, budget,
+                       "swap_last" if mode == 1 else "stable")
+    return n_same, n_steps
+
+
+@pytest.mark.parametrize("kw,budget", [
+    (dict(context=700, window=8), 650),
+    (dict(context=700, window=8, base=synth.BASE_NONE, n_protect_head=4, n_protect_tail=8), 600),
+    (dict(context=1500, window=32, base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=32), 1400),
+    (dict(context=300, window=4, head_dim=64, dtype="f32", n_q_heads=4, n_kv_heads=4), 250),
+    (dict(context=513, window=1, head_dim=64, batch=3), 500),
+    (dict(context=257, window=1), 256),
+], ids=["h2o", "plain-protected", "snapkv", "f32-d64", "bf16-d64", "evict-one"])
+def test_greedy_joint_eviction(B, oracle, kw, budget):
+    wl = small(**kw)
+    lens = None
+    if wl.batch > 1 and wl.context > 400:
+        lens = np.array([wl.context] + [wl.context - 37 * (i + 1) for i in range(wl.batch - 1)], dtype=np.int32)
+    cache = synth.make_cache(wl, seq_lens=lens, base_init="random")
+    n_same, n_steps = joint_check(B, oracle, cache, budget, mode=1 if kw.get("context") == 257 else 0)
+    assert n_same >= 0.9 * n_steps        # near-ties aside, the very sequence of the oracle's greedy
+
+
+def test_greedy_joint_eviction_prefill_block(B, oracle):
+    """The block-wise prefill step (2048 cached + 128 new rows, 128 leave), joint selection."""
+    wl = synth.prefill_block()
+    cache = synth.make_cache(wl, base_init="random")
+    joint_check(B, oracle, cache, wl.budget)
+
+
+def test_greedy_joint_eviction_limits(B):
+    wl = small(context=CAP_JOINT + 64, window=8)
+    dev = H.to_device(synth.make_cache(wl))
+    L = B.layout_for(wl, dev)
+    ws = torch.empty(B.caote_workspace_bytes(L, 100), dtype=torch.uint8, device="cuda")
+    args = lambda: (dev.q, dev.K, dev.V, dev.base, L, 100, 0, torch.empty(2, 2, wl.context, device="cuda"),
+                    torch.empty(2, 2, 100, dtype=torch.int32, device="cuda"),
+                    torch.empty(2, 2, wl.context - 100, dtype=torch.int32, device="cuda"),
+                    torch.empty(2, 2, wl.context - 100, device="cuda"), ws)
+    with pytest.raises(B.CaoteError) as e:
+        B.caote_evict_joint(*args())
+    assert e.value.status == B.EUNSUPPORTED
 
 
 def test_fastcaote_variant(B, oracle):
