@@ -200,6 +200,20 @@ def main():
         append(i)
         B.caote_evict(q, K, V, base, lse_layouts[i % n_layers][1], wl.budget, mode, scores, kept, ws, stream)
 
+    # Greedy selection under the joint error (caote_evict_joint), where the entry point takes
+    # the workload: a second figure, as for row_lse.
+    # (one launch per evicted token and step of the graph: only where few tokens leave)
+    joint_ok = wl.context <= B.JOINT_MAX_CAPACITY and wl.context - wl.budget <= 256 and not args.no_graph
+    if joint_ok:
+        n_ev = wl.context - wl.budget
+        evicted = torch.empty(wl.batch, wl.n_kv_heads, n_ev, dtype=torch.int32, device="cuda")
+        joint_err = torch.empty(wl.batch, wl.n_kv_heads, n_ev, device="cuda")
+
+    def step_joint(i):
+        q, K, V, base = layers[i % n_layers]
+        append(i)
+        B.caote_evict_joint(q, K, V, base, L, wl.budget, mode, scores, kept, evicted, joint_err, ws, stream)
+
     def timed_replay(step_fn):
         """K steps captured once into a HIP graph (the library neither allocates nor
         synchronises; eager launches are launch-bound: six to nine short kernels per step)."""
@@ -242,6 +256,7 @@ def main():
     else:
         dt = timed_replay(step)
         dt_lse = timed_replay(step_lse)
+    dt_joint = timed_replay(step_joint) if joint_ok else None
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = wl.batch * wl.context / (dt / args.steps)
 
@@ -286,6 +301,14 @@ def main():
             "value": wl.batch * wl.context / (dt_lse / args.steps), "unit": "tokens/s",
             "note": "same call with layout.row_lse set (the caller's attention pass supplies the "
                     "softmax normalisers): no first key sweep"}
+
+    if dt_joint is not None:
+        out["joint_selection"] = {
+            "ms_per_step": dt_joint / args.steps * 1e3,
+            "value": wl.batch * wl.context / (dt_joint / args.steps), "unit": "tokens/s",
+            "evicted_per_head": wl.context - wl.budget,
+            "note": "caote_evict_joint: the same step with the greedy selection under the joint "
+                    "error; its steps run one after the other inside one workgroup per head"}
 
     if not args.skip_cpu_baseline:
         import oracle

@@ -177,10 +177,12 @@ caote_status caote_evict(const void* q_window, void* K, void* V, float* base_sco
  * the exact minimiser over all sets is combinatorial, so tokens leave one at a time: each of
  * the N_b - budget steps evicts the scored row j, not yet evicted, with the smallest
  * c_{S + j}; equal errors evict the higher index; a row whose eviction would leave no weight
- * behind has error +INF.  The steps of one (sequence, KV head) run in sequence inside one
- * workgroup: the time grows with (N_b - budget) * N_b, which is why the call is limited to
- * capacity <= CAOTE_JOINT_MAX_CAPACITY and meant for block-wise prefill and generation, where
- * few tokens leave per call.  Only CAOTE_EXACT; budget >= n_protect_head + n_protect_tail.
+ * behind has error +INF.  Every step depends on the one before and needs all value rows of
+ * the head again, so the call enqueues ONE KERNEL PER STEP (capacity - budget of them, each
+ * a few microseconds whatever N_b is, plus one that writes kept_idx): it is meant for
+ * block-wise prefill and generation, where few tokens leave per call, and limited to
+ * capacity <= CAOTE_JOINT_MAX_CAPACITY.  Only CAOTE_EXACT; budget >= n_protect_head +
+ * n_protect_tail.
  *   scores       out, the single-token scores as caote_score writes them
  *   kept_idx     out, as caote_select: ascending, -1 padded
  *   evicted      DEVICE out int32 [batch][n_kv_heads][capacity - budget]: the row evicted at

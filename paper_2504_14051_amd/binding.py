@@ -25,6 +25,7 @@ EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compac
            "caote_append", "caote_evict", "caote_evict_joint", "caote_evict_timed", "caote_phase_name", "caote_last_error",
            "caote_version")
 MAX_PHASES = 16
+JOINT_MAX_CAPACITY = 8192
 
 
 class CaoteError(RuntimeError):

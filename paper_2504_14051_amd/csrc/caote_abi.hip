@@ -126,6 +126,13 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   const size_t row_bytes = (size_t)p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
   const int bud = budget > 0 ? budget : 0;
   p.stage = carve((size_t)BH * bud * (2 * row_bytes + sizeof(float)));
+  if (p.cap <= caote::kJointMaxCap) {
+    p.j_slice = caote::joint_slice_len();
+    p.j_c = ceil_div(p.cap, p.j_slice);
+    p.j_part = (float*)carve((size_t)2 * BH * p.j_c * (4 + caote::kMaxD) * sizeof(float));
+    p.j_u = (float*)carve((size_t)2 * BH * caote::kMaxD * sizeof(float));
+    p.j_rest = (double*)carve((size_t)2 * BH * sizeof(double));
+  }
   return off;
 }
 

@@ -53,6 +53,11 @@ struct Params {
   int hist_in_vscore; // fused call, long cache: k_vscore builds the selection's histogram
   int select_swaps;   // fused call on a short cache: the selection also does the evict-one row swap
   void* stage;        // compaction staging
+  // greedy joint eviction (capacity <= kJointMaxCap); its per-token weights reuse sel_cand
+  float* j_part;      // [2][BH][j_c][4 + kMaxD] per slice and step parity: best candidate and its w (o - v)
+  float* j_u;         // [2][BH][kMaxD]          running sum u, by step parity
+  double* j_rest;     // [2][BH]                 1 - evicted weight, by step parity
+  int j_c, j_slice;   // slices per head, tokens per slice
   int n_split, split_len, Rp, n_vchunk, vchunk_len;
   int vrep, n_vsum;   // value sum: 256-token chunks per workgroup, partial sums per head
   int use_mfma;       // key sweeps on the matrix cores (bf16, head_dim 128, R > 16)
@@ -92,6 +97,23 @@ __device__ __forceinline__ float team_sum(float v) {
 #pragma unroll
   for (int m = TL / 2; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
   return v;
+}
+
+// x + (x of another lane of the same 16-lane row), the lane chosen by a DPP control word.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false);
+  return x + __builtin_bit_cast(float, y);
+}
+// Sum over a team of TL (8 or 16) consecutive lanes, total in every lane: fold the row
+// (lane i <-> 15-i), fold each half (i <-> 7-i), then the two quad exchanges.
+template <int TL>
+__device__ __forceinline__ float team_sum_dpp(float x) {
+  if (TL == 16) x = dpp_add<0x140>(x);   // row_mirror
+  x = dpp_add<0x141>(x);                 // row_half_mirror
+  x = dpp_add<0xB1>(x);                  // quad_perm [1,0,3,2]
+  x = dpp_add<0x4E>(x);                  // quad_perm [2,3,0,1]
+  return x;
 }
 
 // r = q * W + m with 0 <= m < W, for 0 <= r < 2^22: float estimate, one correction step.
@@ -143,6 +165,7 @@ hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook);
+int joint_slice_len();
 hipError_t launch_select_joint(const Params& p, int32_t* order, float* err, int max_evict, hipStream_t s,
                                PhaseHook* hook);
 hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook);

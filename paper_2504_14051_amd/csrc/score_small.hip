@@ -37,23 +37,6 @@ __device__ __forceinline__ void kwiden(const KFrag<float>& f, float (&x)[8]) {
   x[4] = f.hi.x; x[5] = f.hi.y; x[6] = f.hi.z; x[7] = f.hi.w;
 }
 
-// x + (x of another lane of the same 16-lane row), the lane chosen by a DPP control word.
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false);
-  return x + __builtin_bit_cast(float, y);
-}
-// Sum over a team of TL (8 or 16) consecutive lanes, total in every lane: fold the row
-// (lane i <-> 15-i), fold each half (i <-> 7-i), then the two quad exchanges.
-template <int TL>
-__device__ __forceinline__ float team_sum_dpp(float x) {
-  if (TL == 16) x = dpp_add<0x140>(x);   // row_mirror
-  x = dpp_add<0x141>(x);                 // row_half_mirror
-  x = dpp_add<0xB1>(x);                  // quad_perm [1,0,3,2]
-  x = dpp_add<0x4E>(x);                  // quad_perm [2,3,0,1]
-  return x;
-}
-
 template <typename T, int D, int RT>
 __global__ __launch_bounds__(kThreads) void k_rowstats_small(const Params p) {
   constexpr int TL = D / 8;               // lanes that share one key row
