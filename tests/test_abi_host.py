@@ -142,3 +142,30 @@ def test_append_arguments_are_checked_on_the_host(B):
         B.caote_append(fake, fake, None, fake, fake, L, 0, -1, stream=0)
     assert e.value.status == B.EINVAL
     B.caote_append(fake, fake, None, fake, fake, L, 0, 0, stream=0)   # nothing to do: no launch
+
+
+def test_joint_eviction_arguments_are_checked_on_the_host(B):
+    fake = 0x1000
+
+    def call(L, budget, evicted=fake, err=fake):
+        B.caote_evict_joint(fake, fake, fake, fake, L, budget, 0, fake, fake, evicted, err, fake,
+                            stream=0, workspace_bytes=1 << 40)
+
+    with pytest.raises(B.CaoteError) as e:                       # beyond the capacity limit
+        call(good_layout(B, capacity=B.JOINT_MAX_CAPACITY + 1), 100)
+    assert e.value.status == B.EUNSUPPORTED and str(B.JOINT_MAX_CAPACITY) in str(e.value)
+    with pytest.raises(B.CaoteError) as e:                       # defined for the exact score only
+        call(good_layout(B, variant=B.FAST), 100)
+    assert e.value.status == B.EUNSUPPORTED
+    with pytest.raises(B.CaoteError) as e:                       # fewer slots than protected rows
+        call(good_layout(B, n_protect_head=60, n_protect_tail=50), 100)
+    assert e.value.status == B.EINVAL and "protected" in str(e.value)
+    with pytest.raises(B.CaoteError) as e:                       # outputs missing
+        call(good_layout(B), 100, evicted=None)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.CaoteError) as e:
+        call(good_layout(B), 100, err=None)
+    assert e.value.status == B.EINVAL
+    # the header's limit is the binding's
+    hdr = open(os.path.join(ROOT, "include", "caote.h")).read()
+    assert int(re.search(r"#define\s+CAOTE_JOINT_MAX_CAPACITY\s+(\d+)", hdr).group(1)) == B.JOINT_MAX_CAPACITY
