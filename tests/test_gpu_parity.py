@@ -553,3 +553,62 @@ def test_hip_graph_replays_match_eager(B):
         assert torch.equal(g_scores, e_scores), f"replay {rep}: scores differ from the eager call"
         assert torch.equal(g_kept, e_kept), f"replay {rep}: kept indices differ"
         assert torch.equal(g_base, e_base), f"replay {rep}: accumulator differs"
+
+
+def test_hip_graph_replays_of_joint_eviction_match_eager(B):
+    """caote_evict_joint enqueues one kernel per evicted token, with buffers that alternate
+    between steps; captured once and replayed from restored inputs it must give the eager bits."""
+    wl = small(context=600, window=8)
+    budget = 560
+    cache = synth.make_cache(wl, base_init="random")
+    dev = H.to_device(cache)
+    L = B.layout_for(wl, dev)
+    ws = torch.empty(B.caote_workspace_bytes(L, budget), dtype=torch.uint8, device="cuda")
+    Bn, Hkv, cap = dev.K.shape[:3]
+    K0, V0, base0 = dev.K.clone(), dev.V.clone(), dev.base.clone()
+
+    def outputs():
+        return (torch.zeros(Bn, Hkv, cap, device="cuda"),
+                torch.zeros(Bn, Hkv, budget, dtype=torch.int32, device="cuda"),
+                torch.zeros(Bn, Hkv, cap - budget, dtype=torch.int32, device="cuda"),
+                torch.zeros(Bn, Hkv, cap - budget, device="cuda"))
+
+    def run(out, stream=None):
+        B.caote_evict_joint(dev.q, dev.K, dev.V, dev.base, L, budget, 0, *out, ws, stream)
+
+    eager = outputs()
+    run(eager)
+    torch.cuda.synchronize()
+    eK, eV, eb = dev.K.clone(), dev.V.clone(), dev.base.clone()
+
+    def restore():
+        dev.K.copy_(K0)
+        dev.V.copy_(V0)
+        dev.base.copy_(base0)
+
+    got = outputs()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        restore()
+        run(got, side)
+        side.synchronize()
+        restore()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run(got, side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        restore()
+        for t in got:
+            t.zero_()
+        ws.random_(0, 255)                           # nothing may depend on what the workspace held
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("scores", "kept", "evicted", "joint_error"), got, eager):
+            assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager call"
+        n = budget
+        assert torch.equal(dev.K[:, :, :n], eK[:, :, :n]) and torch.equal(dev.V[:, :, :n], eV[:, :, :n])
+        assert torch.equal(dev.base[:, :, :n], eb[:, :, :n])
