@@ -308,7 +308,7 @@ def main():
             "value": wl.batch * wl.context / (dt_joint / args.steps), "unit": "tokens/s",
             "evicted_per_head": wl.context - wl.budget,
             "note": "caote_evict_joint: the same step with the greedy selection under the joint "
-                    "error; its steps run one after the other inside one workgroup per head"}
+                    "error: one kernel per evicted token, each step needs the one before"}
 
     if not args.skip_cpu_baseline:
         import oracle
