@@ -3,10 +3,12 @@
 // their slab.
 //
 // kept_idx is ascending, so rank i reads row kept_idx[i] >= i and writes row i; a
-// row may be overwritten by one rank while another rank still has to read it.  The
-// rows that move are therefore first gathered into staging memory and written back
-// by a second kernel (stream order is the barrier).  Rows that already sit at their
-// rank are not touched.
+// row inside the destination range [0, n_keep) may be overwritten by one rank while
+// another rank still has to read it.  Those source rows are first gathered into staging
+// memory (first kernel); the second kernel writes every destination row, from staging or,
+// for source rows at or beyond n_keep, which nobody writes, straight from the cache (stream
+// order is the barrier).  On a long cache cut to a small budget nearly all kept rows come
+// from beyond n_keep and move once.  Rows that already sit at their rank are not touched.
 //
 // Evict-one sequences in SWAP_LAST mode move a single row (k_swap_last): the last row drops
 // into the hole.  A sequence that evicts any other number of tokens is compacted stably.
@@ -70,6 +72,8 @@ __global__ __launch_bounds__(kThreads) void k_move_rows(const Params p, int row_
   const int32_t* idx = p.kept + (int64_t)bh * p.budget;
   const int src = source_row(p, idx, i, N);
   if (src < 0) return;
+  const bool direct = src >= min(N, p.budget);        // source row outside the destination range
+  if (DIR == 0 && direct) return;
 
   const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
   char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
@@ -86,6 +90,10 @@ __global__ __launch_bounds__(kThreads) void k_move_rows(const Params p, int row_
     *reinterpret_cast<uint4*>(stV + (int64_t)i * row_bytes + ch * 16) =
         *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
     if (ch == 0 && p.base) stB[i] = p.base[(int64_t)bh * p.cap + src];
+  } else if (direct) {
+    *reinterpret_cast<uint4*>(Kb + i * krow + ch * 16) = *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
+    *reinterpret_cast<uint4*>(Vb + i * vrow + ch * 16) = *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
+    if (ch == 0 && p.base) p.base[(int64_t)bh * p.cap + i] = p.base[(int64_t)bh * p.cap + src];
   } else {
     *reinterpret_cast<uint4*>(Kb + i * krow + ch * 16) =
         *reinterpret_cast<const uint4*>(stK + (int64_t)i * row_bytes + ch * 16);
