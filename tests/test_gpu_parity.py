@@ -387,6 +387,24 @@ def test_greedy_joint_eviction_limits(B):
     assert e.value.status == B.EUNSUPPORTED
 
 
+@pytest.mark.parametrize("factor", [8.0, 1.0 / 64], ids=["sharp", "flat"])
+@pytest.mark.parametrize("kw", [
+    dict(window=8),                                                   # matrix-core sweeps
+    dict(window=1, context=1500, budget=1400),                        # few rows, matrix cores
+    dict(window=2, head_dim=64, dtype="f32"),                         # few rows, vector ALUs
+    dict(window=8, head_dim=64, dtype="f32"),                         # two-sweep vector path
+    dict(window=16, base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=16),
+], ids=["mfma", "few-mfma", "few-valu", "generic", "snapkv"])
+def test_sharp_and_flat_softmax(B, oracle, kw, factor):
+    """Logits scaled by 8 (attention collapses onto a few keys, exponents far apart) and by
+    1/64 (nearly uniform attention): the queries carry the factor, a power of two, so the
+    stored values stay exact."""
+    wl = small(**kw)
+    cache = synth.make_cache(wl, base_init="random")
+    cache.q.mul_(factor)
+    full_check(B, oracle, cache, wl.budget)
+
+
 def test_fastcaote_variant(B, oracle):
     wl = small(base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=8)
     full_check(B, oracle, synth.make_cache(wl), wl.budget, variant=1)
