@@ -214,7 +214,9 @@ def main():
         append(i)
         B.caote_evict_joint(q, K, V, base, L, wl.budget, mode, scores, kept, evicted, joint_err, ws, stream)
 
-    def timed_replay(step_fn):
+    replays = []       # per timed_replay call: ms per step of the extra replays
+
+    def timed_replay(step_fn, n_again=0):
         """K steps captured once into a HIP graph (the library neither allocates nor
         synchronises; eager launches are launch-bound: six to nine short kernels per step)."""
         nonlocal stream
@@ -240,6 +242,14 @@ def main():
             g_timed.replay()
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
+            # the same graph a few more times: the spread of the per-step time between replays
+            again = []
+            for _ in range(n_again):
+                t1 = time.perf_counter()
+                g_timed.replay()
+                torch.cuda.synchronize()
+                again.append((time.perf_counter() - t1) / args.steps * 1e3)
+            replays.append(again)
         stream = outer
         return dt
 
@@ -254,9 +264,30 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
     else:
-        dt = timed_replay(step)
+        dt = timed_replay(step, n_again=4)
         dt_lse = timed_replay(step_lse)
     dt_joint = timed_replay(step_joint) if joint_ok else None
+
+    # The three calls one after the other (same kernels minus what only the fused call can
+    # merge), and a plain streaming read of the same K and V buffers: the empirical ceiling.
+    def step_separate(i):
+        q, K, V, base = layers[i % n_layers]
+        append(i)
+        B.caote_score(q, K, V, base, L, scores, ws, stream)
+        B.caote_select(scores, L, wl.budget, kept, ws, stream)
+        B.caote_compact(K, V, base, kept, L, wl.budget, mode, ws, stream)
+
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+
+    def step_read(i):
+        _, K, V, _ = layers[i % n_layers]
+        B.caote_read_stream(K, K.numel() * K.element_size(), sink, stream)
+        B.caote_read_stream(V, V.numel() * V.element_size(), sink, stream)
+
+    dt_sep = dt_read = None
+    if not args.no_graph:
+        dt_sep = timed_replay(step_separate)
+        dt_read = timed_replay(step_read)
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = wl.batch * wl.context / (dt / args.steps)
 
@@ -302,6 +333,17 @@ def main():
             "note": "same call with layout.row_lse set (the caller's attention pass supplies the "
                     "softmax normalisers): no first key sweep"}
 
+    if replays and replays[0]:
+        out["ms_per_step_replays"] = sorted(replays[0])
+    if dt_sep is not None:
+        out["separate_calls"] = {"ms_per_step": dt_sep / args.steps * 1e3,
+                                 "note": "caote_score, caote_select, caote_compact one after the other"}
+    if dt_read is not None:
+        kv_bytes = 2 * layers[0][1].numel() * layers[0][1].element_size()
+        out["read_stream"] = {"achieved": kv_bytes / (dt_read / args.steps) / 1e9, "unit": "GB/s",
+                              "bytes_per_step": kv_bytes,
+                              "note": "plain streaming read of the same K and V buffers, same rotation: "
+                                      "the rate no sweep over them can exceed on this device"}
     if dt_joint is not None:
         out["joint_selection"] = {
             "ms_per_step": dt_joint / args.steps * 1e3,

@@ -211,6 +211,12 @@ caote_status caote_evict_timed(const void* q_window, void* K, void* V, float* ba
                                int32_t* n_phases);
 const char* caote_phase_name(int32_t i);
 
+/* Measurement aid: reads `bytes` of device memory at `buf` once with plain 16-byte loads and
+ * discards them: the read rate a streaming kernel reaches on this device, the empirical
+ * ceiling beside the published HBM peak.  buf 16-byte aligned, bytes a multiple of 16;
+ * sink: DEVICE, 4 bytes, in practice never written (it keeps the loads alive).           */
+caote_status caote_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream);
+
 /* Text of the calling thread's most recent failure ("" if none).  The pointer
  * stays valid until that thread's next failing call.                               */
 const char* caote_last_error(void);

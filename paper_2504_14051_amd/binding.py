@@ -22,7 +22,7 @@ EXACT, FAST = 0, 1
 COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
 
 EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
-           "caote_append", "caote_evict", "caote_evict_joint", "caote_evict_timed", "caote_phase_name", "caote_last_error",
+           "caote_append", "caote_evict", "caote_evict_joint", "caote_evict_timed", "caote_read_stream", "caote_phase_name", "caote_last_error",
            "caote_version")
 MAX_PHASES = 16
 JOINT_MAX_CAPACITY = 8192
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
         L.caote_evict_timed.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp,
                                         ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         L.caote_evict_timed.restype = ctypes.c_int
+        L.caote_read_stream.argtypes = [vp, sz, vp, vp]
+        L.caote_read_stream.restype = ctypes.c_int
         L.caote_phase_name.argtypes = [i32]
         L.caote_phase_name.restype = ctypes.c_char_p
         L.caote_last_error.argtypes = []
@@ -207,6 +209,11 @@ def caote_evict_timed(q_window, K, V, base_score, layout: Layout, budget: int, m
                                    _ptr(kept_idx), _ptr(workspace), wb, _stream(stream), ms,
                                    ctypes.byref(n)))
     return [(lib().caote_phase_name(i).decode(), float(ms[i])) for i in range(n.value)]
+
+
+def caote_read_stream(buf, nbytes: int, sink, stream=None) -> None:
+    """Measurement aid: one plain streaming read of `nbytes` at `buf`."""
+    _check(lib().caote_read_stream(_ptr(buf), nbytes, _ptr(sink), _stream(stream)))
 
 
 def layout_for(wl, cache_dev, row_lse=None) -> Layout:

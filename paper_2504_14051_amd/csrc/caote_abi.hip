@@ -358,6 +358,13 @@ caote_status caote_evict_timed(const void* q_window, void* K, void* V, float* ba
   return CAOTE_OK;
 }
 
+caote_status caote_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream) {
+  if (!buf || !sink) return fail(CAOTE_EINVAL, "buf and sink must not be NULL");
+  if (((uintptr_t)buf % 16) != 0 || bytes % 16 != 0)
+    return fail(CAOTE_EINVAL, "buf must be 16-byte aligned and bytes a multiple of 16");
+  return device_status(caote::launch_read_stream(buf, bytes, sink, (hipStream_t)hip_stream), "read_stream");
+}
+
 const char* caote_phase_name(int32_t i) {
   return i >= 0 && i < CAOTE_MAX_PHASES && g_phase_names[i] ? g_phase_names[i] : "";
 }

@@ -169,6 +169,7 @@ int joint_slice_len();
 hipError_t launch_select_joint(const Params& p, int32_t* order, float* err, int max_evict, hipStream_t s,
                                PhaseHook* hook);
 hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook);
+hipError_t launch_read_stream(const void* buf, size_t bytes, void* sink, hipStream_t s);
 hipError_t launch_append(const Params& p, const void* k_new, const void* v_new, int n_at, int n_new,
                          hipStream_t s);
 
