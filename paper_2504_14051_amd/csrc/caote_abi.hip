@@ -96,8 +96,12 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.small_r = !p.use_mfma && p.R <= 8;
   p.s_rows = p.R <= 4 ? 4 : 8;
   p.s_pitch = (int)align_up((size_t)p.cap, 4);
-  p.split_len = p.use_mfma ? chunk_len(p.R > 128 ? 256 : 512, 128, 1 << 20) : (p.R <= 8 ? (p.dtype == CAOTE_BF16 && p.D == 128 ? chunk_len(768, 128, 8192) : chunk_len(2048, 128, 8192))
-                           : chunk_len(1024, 256, 8192));
+  if (p.use_mfma)                                         // one or two workgroups per compute unit
+    p.split_len = chunk_len(p.R > 128 ? 256 : 512, 128, 1 << 20);
+  else if (p.R <= 8)                                      // few rows: matrix cores (bf16, d 128) or vector ALUs
+    p.split_len = p.dtype == CAOTE_BF16 && p.D == 128 ? chunk_len(768, 128, 8192) : chunk_len(2048, 128, 8192);
+  else
+    p.split_len = chunk_len(1024, 256, 8192);
   p.n_split = ceil_div(p.cap, p.split_len);
   p.vchunk_len = caote::kVChunk;
   p.n_vchunk = ceil_div(p.cap, p.vchunk_len);
