@@ -320,7 +320,7 @@ __global__ __launch_bounds__(kThreads) void k_vscore(const Params p) {
       float d2 = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) { const float t = x[e] - of[e]; d2 = fmaf(t, t, d2); }
-      d2 = team_sum<TL>(d2);
+      d2 = team_sum_dpp<TL>(d2);
       if (tl == 0) d_lds[(it0 + u) * RPI + team] = sqrtf(d2);
     }
   }

@@ -169,3 +169,12 @@ def test_joint_eviction_arguments_are_checked_on_the_host(B):
     # the header's limit is the binding's
     hdr = open(os.path.join(ROOT, "include", "caote.h")).read()
     assert int(re.search(r"#define\s+CAOTE_JOINT_MAX_CAPACITY\s+(\d+)", hdr).group(1)) == B.JOINT_MAX_CAPACITY
+
+
+def test_read_stream_arguments_are_checked_on_the_host(B):
+    fake = 0x1000
+    for args in ((None, 16, fake), (fake, 16, None), (fake + 4, 16, fake), (fake, 20, fake)):
+        with pytest.raises(B.CaoteError) as e:
+            B.caote_read_stream(*args, stream=0)
+        assert e.value.status == B.EINVAL
+    B.caote_read_stream(fake, 0, fake, stream=0)                 # nothing to read: no launch

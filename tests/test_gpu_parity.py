@@ -630,3 +630,17 @@ def test_hip_graph_replays_of_joint_eviction_match_eager(B):
         n = budget
         assert torch.equal(dev.K[:, :, :n], eK[:, :, :n]) and torch.equal(dev.V[:, :, :n], eV[:, :, :n])
         assert torch.equal(dev.base[:, :, :n], eb[:, :, :n])
+
+
+def test_read_stream_probe_runs_and_writes_nothing(B):
+    """The measurement aid only reads: ragged sizes, the sink keeps its value."""
+    buf = torch.arange(0, (1 << 20) + 48, dtype=torch.uint8, device="cuda")
+    sink = torch.full((1,), 1234, dtype=torch.int32, device="cuda")
+    for nbytes in (16, 4096, 32768 + 16, 1 << 20, (1 << 20) + 48):
+        B.caote_read_stream(buf, nbytes, sink)
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 1234
+    with pytest.raises(B.CaoteError):
+        B.caote_read_stream(buf, 24, sink)
+    with pytest.raises(B.CaoteError):
+        B.caote_read_stream(buf.data_ptr() + 8, 16, sink)
