@@ -644,3 +644,35 @@ def test_read_stream_probe_runs_and_writes_nothing(B):
         B.caote_read_stream(buf, 24, sink)
     with pytest.raises(B.CaoteError):
         B.caote_read_stream(buf.data_ptr() + 8, 16, sink)
+
+
+def test_calls_in_flight_on_separate_streams_match_serial(B):
+    """The library keeps no state of its own: calls on different caches, each with its own
+    workspace and stream, may overlap and must give the bits of the same calls run alone."""
+    wl = synth.llama3_8b_4k()
+    caches = [synth.make_cache(wl.with_(seed=wl.seed + 100 * i), base_init="random") for i in range(3)]
+
+    def run(devs, streams):
+        outs = []
+        for dev, st in zip(devs, streams):
+            L = B.layout_for(wl, dev)
+            ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
+            Bn, Hkv, cap = dev.K.shape[:3]
+            scores = torch.zeros(Bn, Hkv, cap, device="cuda")
+            kept = torch.zeros(Bn, Hkv, wl.budget, dtype=torch.int32, device="cuda")
+            outs.append((scores, kept, ws, L))
+        torch.cuda.synchronize()
+        for dev, st, (scores, kept, ws, L) in zip(devs, streams, outs):   # enqueued back to back
+            B.caote_evict(dev.q, dev.K, dev.V, dev.base, L, wl.budget, 0, scores, kept, ws, st)
+        torch.cuda.synchronize()
+        return [(s.cpu(), k.cpu(), d.K.cpu(), d.V.cpu(), d.base.cpu()) for (s, k, _, _), d in zip(outs, devs)]
+
+    serial = run([H.to_device(c) for c in caches], [None] * 3)
+    streams = [torch.cuda.Stream() for _ in caches]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    overlapped = run([H.to_device(c) for c in caches], streams)
+    for i, (a, b) in enumerate(zip(serial, overlapped)):
+        for name, x, y in zip(("scores", "kept", "K", "V", "base"), a, b):
+            n = wl.budget if name in ("K", "V", "base") else x.shape[2]
+            assert torch.equal(x[:, :, :n], y[:, :, :n]), f"call {i}: {name} differs when the calls overlap"
