@@ -27,16 +27,23 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
+def swap_last(wl):
+    """Evict-one calls (generation) move one row per head: the last row drops into the hole."""
+    return wl.window == 1 and wl.budget == wl.context - 1
+
+
 def algorithmic_bytes(wl, n_tokens=None):
     """HBM bytes the method must move for one layer (K and V once, window queries, three
-    fp32 per-token vectors, gather read + write of the kept rows)."""
+    fp32 per-token vectors, gather read + write of the kept rows, or of the one row that an
+    evict-one call in swap-last mode moves)."""
     N = wl.context if n_tokens is None else n_tokens
     esz = 2 if wl.dtype == "bf16" else 4
     bh = wl.batch * wl.n_kv_heads
     kv = 2 * bh * N * wl.head_dim * esz
     q = wl.batch * wl.n_q_heads * wl.window * wl.head_dim * esz
     vec = 3 * bh * N * 4
-    comp = 2 * 2 * bh * min(wl.budget, N) * wl.head_dim * esz
+    rows_moved = 1 if swap_last(wl) else min(wl.budget, N)
+    comp = 2 * 2 * bh * rows_moved * wl.head_dim * esz
     return {"kv": kv, "q": q, "vectors": vec, "compact": comp, "total": kv + q + vec + comp}
 
 
@@ -58,6 +65,8 @@ def phase_bytes(wl, name, fused_value_sum=False):
         "value_sum": k_bytes + 2 * vec,
         "value_score": k_bytes + 2 * vec,
         "value_sweeps": k_bytes + 3 * vec,
+        "value_side": k_bytes + 3 * vec,                 # V once, logits / mass and accumulator in, partial distances out
+        "value_combine": 4 * vec,
         "value_final": bh * (d + 1) * 4 * 2,              # at least: one partial sum in, the total out
         "select": vec + bh * wl.budget * 4,
         "select_hist": vec,
@@ -76,7 +85,7 @@ def phase_bytes(wl, name, fused_value_sum=False):
 PHASE_KERNELS = {
     "key_rowstats": r"k_logits_\w+<.*, 0>$", "key_colsum": r"k_logits_\w+<.*, [12]>$",
     "merge_stats": r"k_merge_stats", "value_sum": r"k_vsum", "value_final": r"k_vfinal",
-    "value_score": r"k_vscore", "select_hist": r"k_select_hist", "select_span": r"k_select_span",
+    "value_score": r"k_vscore", "value_side": r"k_vside", "value_combine": r"k_vcombine", "select_hist": r"k_select_hist", "select_span": r"k_select_span",
     "select_emit": r"k_select_emit", "compact_gather": r"k_move_rows<0>", "compact_scatter": r"k_move_rows<1>",
 }
 
@@ -128,7 +137,7 @@ def main():
     wl = synth.WORKLOADS[args.workload]()
     host = synth.make_cache(wl)
     n_layers = max(1, args.layers)
-    mode = B.COMPACT_SWAP_LAST if wl.window == 1 and wl.budget == wl.context - 1 else B.COMPACT_STABLE
+    mode = B.COMPACT_SWAP_LAST if swap_last(wl) else B.COMPACT_STABLE
 
     # Layer 0 is the generator's output; the others are the same tensors with the KV heads
     # rotated (same statistics, different addresses), so each step streams fresh HBM lines.

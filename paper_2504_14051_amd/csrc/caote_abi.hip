@@ -111,6 +111,11 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.halo = p.base_mode == CAOTE_BASE_SNAPKV ? p.pool / 2 : 0;
   p.fuse_v = p.use_mfma && p.halo <= 64;
   p.n_vpart = p.fuse_v ? p.n_split : p.n_vsum;
+  // short caches whose value sweeps are not fused into the key sweep: V read once, rows held
+  // in registers between their two uses
+  // (k_vside addresses the rows of a head with 32-bit byte offsets)
+  p.vside_cs = (p.dtype == CAOTE_BF16 && p.D == 128 && !p.fuse_v && (int64_t)p.cap * p.vsn * 2 < (1ll << 31))
+                   ? caote::vside_column_split(p.cap) : 0;
 
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return ws ? ws + o : nullptr; };
@@ -130,6 +135,8 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   const size_t row_bytes = (size_t)p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
   const int bud = budget > 0 ? budget : 0;
   p.stage = carve((size_t)BH * bud * (2 * row_bytes + sizeof(float)));
+  p.merge_in_vside = p.vside_cs && p.small_r;
+  p.d2part = (float*)carve((size_t)p.vside_cs * BH * p.cap * sizeof(float));
   if (p.cap <= caote::kJointMaxCap) {
     p.j_slice = caote::joint_slice_len();
     p.j_c = ceil_div(p.cap, p.j_slice);
@@ -160,7 +167,8 @@ caote_status do_score(Params& p, hipStream_t s, caote::PhaseHook* hook = nullptr
                                                                     : caote::launch_score_small(p, s, hook))
                               : caote::launch_score_generic(p, s, hook);
   if (e != hipSuccess) return device_status(e, "score (key sweeps)");
-  return device_status(caote::launch_value_passes(p, s, hook), "score (value sweeps)");
+  return device_status(p.vside_cs ? caote::launch_value_side(p, s, hook) : caote::launch_value_passes(p, s, hook),
+                       "score (value sweeps)");
 }
 
 // Measurement aid: events recorded between the kernels of one call.
@@ -216,7 +224,7 @@ caote_status caote_score(const void* q_window, const void* K, const void* V, flo
   if (st != CAOTE_OK) return st;
   p.q = q_window; p.K = const_cast<void*>(K); p.V = const_cast<void*>(V);
   p.base = base_score; p.scores = scores;
-  if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
+  if (layout->base == CAOTE_BASE_H2O && !p.vside_cs) p.h = base_score;   // (k_vside keeps h apart)
   return do_score(p, (hipStream_t)hip_stream);
 }
 
@@ -301,13 +309,14 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
   p.mode = mode;
   // the merge of the row statistics (or, on the matrix-core path, the second sweep) clears
   // the selection's counters on its way
-  p.hist_zeroed = (!p.lse_in || p.use_mfma) ? 1 : 0;
+  p.hist_zeroed = ((!p.lse_in && !p.merge_in_vside) || p.use_mfma) ? 1 : 0;
   // up to 128 scoring workgroups per head add to the same few dozen bins: beyond that the
   // serialised device atomics outlast the kernel, and a histogram kernel of its own is faster
   p.hist_in_vscore = (p.cap > 16384 && p.cap <= 32768 && p.hist_zeroed) ? 1 : 0;
   p.select_swaps = p.cap <= 16384 ? 1 : 0;  // (the one-workgroup selections of launch_select)
+  p.combine_in_select = (p.vside_cs && !joint) ? 1 : 0;   // (k_vside caches are short: one-workgroup selection)
   if (joint) p.hist_in_vscore = p.select_swaps = 0;
-  if (layout->base == CAOTE_BASE_H2O) p.h = base_score;
+  if (layout->base == CAOTE_BASE_H2O && !p.vside_cs) p.h = base_score;
   st = do_score(p, s, hook);
   if (st != CAOTE_OK) return st;
   if (joint) {

@@ -15,6 +15,7 @@ constexpr int kHistBins = 4096;   // selection histogram: top 12 bits of the sco
 constexpr int kHistShift = 20;
 constexpr int kSelSpan = 2048;    // tokens per workgroup in the selection kernels
 constexpr int kMaxSpans = 1024;   // spans per head the selection supports (2M tokens)
+constexpr int kVSideSlots = 34;   // short caches: value rows a lane keeps in registers (k_vside)
 constexpr int kJointMaxCap = CAOTE_JOINT_MAX_CAPACITY;   // greedy joint eviction: weights of a head fit LDS
 
 // Everything a kernel needs to know about one call.  Passed by value.
@@ -62,6 +63,10 @@ struct Params {
   int vrep, n_vsum;   // value sum: 256-token chunks per workgroup, partial sums per head
   int use_mfma;       // key sweeps on the matrix cores (bf16, head_dim 128, R > 16)
   int halo;           // SnapKV: pooling half-width (0 otherwise)
+  int vside_cs;       // short cache: column workgroups per head of the one-read value kernel (0: not used)
+  float* d2part;      // [vside_cs][BH][cap]   per column slice: its part of ||v_j - o||^2
+  int merge_in_vside; // few query rows: k_vside merges the row statistics itself (no merge kernel)
+  int combine_in_select;  // fused call: the one-workgroup selection adds the column slices up (no k_vcombine)
   int fuse_v;         // the second key sweep also forms the value partial sums (one per split)
   int n_vpart;        // partial sums per head in opart / zpart: n_split if fuse_v, else n_vsum
 };
@@ -105,14 +110,15 @@ __device__ __forceinline__ float dpp_add(float x) {
   const int y = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false);
   return x + __builtin_bit_cast(float, y);
 }
-// Sum over a team of TL (8 or 16) consecutive lanes, total in every lane: fold the row
+// Sum over a team of TL (2, 4, 8 or 16) consecutive lanes, total in every lane: fold the row
 // (lane i <-> 15-i), fold each half (i <-> 7-i), then the two quad exchanges.
 template <int TL>
 __device__ __forceinline__ float team_sum_dpp(float x) {
-  if (TL == 16) x = dpp_add<0x140>(x);   // row_mirror
-  x = dpp_add<0x141>(x);                 // row_half_mirror
+  static_assert(TL == 2 || TL == 4 || TL == 8 || TL == 16, "team size");
+  if (TL >= 16) x = dpp_add<0x140>(x);   // row_mirror
+  if (TL >= 8) x = dpp_add<0x141>(x);    // row_half_mirror
   x = dpp_add<0xB1>(x);                  // quad_perm [1,0,3,2]
-  x = dpp_add<0x4E>(x);                  // quad_perm [2,3,0,1]
+  if (TL >= 4) x = dpp_add<0x4E>(x);     // quad_perm [2,3,0,1]
   return x;
 }
 
@@ -133,6 +139,39 @@ __device__ __forceinline__ float row_lse2(const Params& p, int b, int hk, int bh
     return p.lse_in[((int64_t)b * p.Hq + hk * p.G + g) * p.W + iw] * 1.4426950408889634f;
   }
   return p.lse2[(int64_t)bh * p.Rp + r];
+}
+
+// log2-domain normaliser of query row r from the partial (max, sum) pairs that the first key
+// sweep left per split: lse2_r = log2 sum_j exp2(t_rj).
+__device__ __forceinline__ float merged_lse2(const Params& p, int bh, int r, int N) {
+  const int ns = (N + p.split_len - 1) / p.split_len;
+  const float* st = p.stats + ((int64_t)bh * p.n_split * p.Rp + r) * 2;
+  float M = -INFINITY;
+  for (int s = 0; s < ns; ++s) M = fmaxf(M, st[(int64_t)s * p.Rp * 2]);
+  float L = 0.f;
+  for (int s = 0; s < ns; ++s) {
+    const float ms = st[(int64_t)s * p.Rp * 2];
+    if (ms > -INFINITY) L += st[(int64_t)s * p.Rp * 2 + 1] * exp2f(ms - M);
+  }
+  return L > 0.f ? M + log2f(L) : INFINITY;
+}
+
+// Score of token j from what k_vside left: c_j = h_j / (Z - h_j) * sqrt(sum over the column
+// slices of their part of ||v_j - o||^2) (Sec. 3.2), +INF for protected rows and for a lone
+// scored token.  Also writes the score and, for H2O, the updated accumulator.
+__device__ __forceinline__ float combine_score(const Params& p, int bh, int j, int N) {
+  const int lo = min(p.ph, N), hi = max(lo, N - p.pt);
+  const float Z = p.osum[(int64_t)bh * (kMaxD + 1) + kMaxD];
+  const float hj = p.h[(int64_t)bh * p.cap + j];
+  float out = INFINITY;
+  if (j >= lo && j < hi && hi - lo > 1) {
+    float q = 0.f;
+    for (int c = 0; c < p.vside_cs; ++c) q += p.d2part[((int64_t)c * p.B * p.Hkv + bh) * p.cap + j];
+    out = Z > 0.f ? hj / fmaxf(Z - hj, 1.17549435e-38f) * sqrtf(q) : 0.f;
+  }
+  p.scores[(int64_t)bh * p.cap + j] = out;
+  if (p.base_mode == CAOTE_BASE_H2O) p.base[(int64_t)bh * p.cap + j] = hj;   // the accumulator, all rows
+  return out;
 }
 
 // Clears the per-head counters that later kernels of the same call accumulate into.
@@ -164,6 +203,8 @@ hipError_t launch_score_small(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
+int vside_column_split(int cap);
+hipError_t launch_value_side(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook);
 int joint_slice_len();
 hipError_t launch_select_joint(const Params& p, int32_t* order, float* err, int max_evict, hipStream_t s,

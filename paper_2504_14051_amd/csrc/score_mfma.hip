@@ -632,7 +632,8 @@ __global__ __launch_bounds__(kFewWaves * kWave) void k_rowstats_few_mfma(const P
 hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook) {
   hipLaunchKernelGGL(k_rowstats_few_mfma, dim3(p.n_split, p.B * p.Hkv), dim3(kFewWaves * kWave), 0, s, p);
   mark(hook, "key_rowstats");
-  if (p.lse_in) return hipGetLastError();   // the caller's normalisers: nothing to merge
+  // the caller's normalisers: nothing to merge; short caches: the value kernel merges
+  if (p.lse_in || p.merge_in_vside) return hipGetLastError();
   return launch_merge_stats(p, s, hook);
 }
 

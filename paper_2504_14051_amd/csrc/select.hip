@@ -395,6 +395,31 @@ __device__ __forceinline__ int block_excl_scan_1024(int v, int* wave_tot, int& t
   return before + inc - v;
 }
 
+// Evict-one in swap-last mode (fused call): the last row of K, V and the accumulator drops
+// into the hole.  Called by all threads of the head's workgroup.
+__device__ __forceinline__ void swap_last_row(const Params& p, int bh, int b, int hk, int hole, int N,
+                                              int row_bytes) {
+  const int tid = threadIdx.x;
+  const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
+  char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
+  char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
+  const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
+  const int cpr = row_bytes / 16;
+  if (tid < cpr)
+    *reinterpret_cast<uint4*>(Kb + hole * krow + tid * 16) = *reinterpret_cast<const uint4*>(Kb + (N - 1) * krow + tid * 16);
+  else if (tid < 2 * cpr)
+    *reinterpret_cast<uint4*>(Vb + hole * vrow + (tid - cpr) * 16) =
+        *reinterpret_cast<const uint4*>(Vb + (N - 1) * vrow + (tid - cpr) * 16);
+  else if (tid == 2 * cpr && p.base)        // (combine_in_select: the accumulator row as k_vside left it)
+    p.base[(int64_t)bh * p.cap + hole] = (p.combine_in_select ? p.h : p.base)[(int64_t)bh * p.cap + N - 1];
+}
+
+// The score of token j: from memory or, in the fused call on a short cache, put together here
+// from the column slices that k_vside left (and written out on the way).
+__device__ __forceinline__ float score_at(const Params& p, const float* sc, int bh, int j, int N) {
+  return p.combine_in_select ? combine_score(p, bh, j, N) : sc[j];
+}
+
 __global__ __launch_bounds__(kST) void k_select_small(const Params p, int row_bytes) {
   const int bh = blockIdx.x, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
@@ -403,6 +428,8 @@ __global__ __launch_bounds__(kST) void k_select_small(const Params p, int row_by
   int32_t* out = p.kept + (int64_t)bh * k;
   if (N <= k) {                           // nothing to evict: identity, -1 padded
     for (int i = tid; i < k; i += kST) out[i] = i < N ? i : -1;
+    if (p.combine_in_select)              // the scores are still owed
+      for (int j = tid; j < N; j += kST) combine_score(p, bh, j, N);
     return;
   }
   __shared__ int hist[kHistBins];
@@ -418,7 +445,33 @@ __global__ __launch_bounds__(kST) void k_select_small(const Params p, int row_by
 #pragma unroll
   for (int e = 0; e < kSPer; ++e) {
     valid[e] = j0 + e < N;
-    key[e] = valid[e] ? float_key(sc[j0 + e]) : 0u;
+    key[e] = valid[e] ? float_key(score_at(p, sc, bh, j0 + e, N)) : 0u;
+  }
+  // ---- one token leaves (generation): the smallest key goes, among equal keys the highest
+  // index; no histogram, one reduction ----------------------------------------------------
+  if (N - k == 1) {
+    __shared__ unsigned long long wave_min[kSW];
+    unsigned long long best = ~0ull;      // key in the high word, ~index in the low word
+#pragma unroll
+    for (int e = 0; e < kSPer; ++e)
+      if (valid[e]) {
+        const unsigned long long c = ((unsigned long long)key[e] << 32) | (uint32_t)~(uint32_t)(j0 + e);
+        best = c < best ? c : best;
+      }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const unsigned long long c = __shfl_xor(best, o, kWave);
+      best = c < best ? c : best;
+    }
+    if ((tid & 63) == 0) wave_min[tid >> 6] = best;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kSW; ++w) best = wave_min[w] < best ? wave_min[w] : best;
+    const int hole = (int)~(uint32_t)best;
+    for (int i = tid; i < k; i += kST) out[i] = i < hole ? i : i + 1;
+    if (p.select_swaps && p.mode == CAOTE_COMPACT_SWAP_LAST && hole != N - 1)
+      swap_last_row(p, bh, b, hk, hole, N, row_bytes);
+    return;
   }
 #pragma unroll
   for (int u = 0; u < kHistBins / kST; ++u) hist[tid + u * kST] = 0;
@@ -513,18 +566,7 @@ __global__ __launch_bounds__(kST) void k_select_small(const Params p, int row_by
     __syncthreads();
     const int hole = s_hole;
     if (hole < 0 || hole == N - 1) return;
-    const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
-    char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
-    char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
-    const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
-    const int cpr = row_bytes / 16;
-    if (tid < cpr)
-      *reinterpret_cast<uint4*>(Kb + hole * krow + tid * 16) = *reinterpret_cast<const uint4*>(Kb + (N - 1) * krow + tid * 16);
-    else if (tid < 2 * cpr)
-      *reinterpret_cast<uint4*>(Vb + hole * vrow + (tid - cpr) * 16) =
-          *reinterpret_cast<const uint4*>(Vb + (N - 1) * vrow + (tid - cpr) * 16);
-    else if (tid == 2 * cpr && p.base)
-      p.base[(int64_t)bh * p.cap + hole] = p.base[(int64_t)bh * p.cap + N - 1];
+    swap_last_row(p, bh, b, hk, hole, N, row_bytes);
   }
 }
 
@@ -542,6 +584,8 @@ __global__ __launch_bounds__(kST) void k_select_one(const Params p, int row_byte
   int32_t* out = p.kept + (int64_t)bh * k;
   if (N <= k) {                           // nothing to evict: identity, -1 padded
     for (int i = tid; i < k; i += kST) out[i] = i < N ? i : -1;
+    if (p.combine_in_select)              // the scores are still owed
+      for (int j = tid; j < N; j += kST) combine_score(p, bh, j, N);
     return;
   }
   __shared__ int hist[kHistBins];
@@ -557,7 +601,7 @@ __global__ __launch_bounds__(kST) void k_select_one(const Params p, int row_byte
 #pragma unroll
     for (int e = 0; e < kSPer; ++e) {
       const int j = u * kSmallCap + tid * kSPer + e;
-      key[u][e] = j < N ? float_key(sc[j]) : 0u;
+      key[u][e] = j < N ? float_key(score_at(p, sc, bh, j, N)) : 0u;
     }
 #pragma unroll
   for (int u = 0; u < kHistBins / kST; ++u) hist[tid + u * kST] = 0;
@@ -667,18 +711,7 @@ __global__ __launch_bounds__(kST) void k_select_one(const Params p, int row_byte
     __syncthreads();
     const int hole = s_hole;
     if (hole < 0 || hole == N - 1) return;
-    const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
-    char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
-    char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
-    const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
-    const int cpr = row_bytes / 16;
-    if (tid < cpr)
-      *reinterpret_cast<uint4*>(Kb + hole * krow + tid * 16) = *reinterpret_cast<const uint4*>(Kb + (N - 1) * krow + tid * 16);
-    else if (tid < 2 * cpr)
-      *reinterpret_cast<uint4*>(Vb + hole * vrow + (tid - cpr) * 16) =
-          *reinterpret_cast<const uint4*>(Vb + (N - 1) * vrow + (tid - cpr) * 16);
-    else if (tid == 2 * cpr && p.base)
-      p.base[(int64_t)bh * p.cap + hole] = p.base[(int64_t)bh * p.cap + N - 1];
+    swap_last_row(p, bh, b, hk, hole, N, row_bytes);
   }
 }
 

@@ -405,6 +405,29 @@ def test_sharp_and_flat_softmax(B, oracle, kw, factor):
     full_check(B, oracle, cache, wl.budget)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(window=1, context=2176, budget=2100),                          # two column workgroups, full
+    dict(window=1, context=2177, budget=2000),                          # four
+    dict(window=2, context=4352, budget=4000, batch=1),                 # four, full
+    dict(window=1, context=5000, budget=4999, batch=1),                 # eight
+    dict(window=1, context=8704, budget=8000, batch=1, base=synth.BASE_NONE),
+    dict(window=1, context=8705, budget=8000, batch=1),                 # beyond: the streaming value kernels
+    dict(window=4, context=3000, budget=2500, batch=1),                 # 16 query rows: two vector-ALU key sweeps
+    dict(window=4, context=3000, budget=2500, batch=1, base=synth.BASE_SNAPKV, pool_kernel=9, n_protect_tail=4),
+    dict(window=1, context=2500, budget=2400, base=synth.BASE_SNAPKV, pool_kernel=301, n_protect_head=3),
+], ids=["cs2-full", "cs4", "cs4-full", "cs8", "cs8-full", "streaming", "generic-h2o", "generic-snapkv", "wide-pool"])
+@pytest.mark.parametrize("variant", [0, 1], ids=["exact", "fast"])
+def test_value_side_column_splits(B, oracle, kw, variant):
+    """Short caches keep a head's value rows in registers, a head cut by columns into 2, 4 or
+    8 workgroups: every split at its size limits, both variants, every base mode."""
+    wl = small(**kw)
+    lens = None
+    if wl.batch > 1:
+        lens = np.array([wl.context, wl.context - 129], dtype=np.int32)
+    cache = synth.make_cache(wl, seq_lens=lens, base_init="random")
+    full_check(B, oracle, cache, wl.budget, mode=1 if wl.budget == wl.context - 1 else 0, variant=variant)
+
+
 def test_fastcaote_variant(B, oracle):
     wl = small(base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=8)
     full_check(B, oracle, synth.make_cache(wl), wl.budget, variant=1)
