@@ -147,19 +147,19 @@ __global__ __launch_bounds__(kJT) void k_joint_step(const Params p, int32_t* ord
   float* alpha = reinterpret_cast<float*>(p.sel_cand) + (int64_t)bh * p.cap;
   const float* os = p.osum + (int64_t)bh * (kMaxD + 1);
   const float* wsrc = t == 0 ? p.h + (int64_t)bh * p.cap : alpha;
+  // (every pass loads: a pass beyond the slice re-reads a scored row and is marked gone; loads
+  // under a lane-dependent condition would be waited for one by one)
   float x[kJPass][8], al[kJPass], o[8];
 #pragma unroll
   for (int k = 0; k < kJPass; ++k) {
     const int j = s0 + team + k * NT;
-    if (j < s1) {
-      load8(Vb + (int64_t)j * p.vsn, x[k]);
-      al[k] = wsrc[j];
-    } else {
-      al[k] = -1.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x[k][e] = 0.f;
-    }
+    const int jj = j < s1 ? j : g.lo;
+    load8(Vb + (int64_t)jj * p.vsn, x[k]);
+    al[k] = wsrc[jj];
   }
+#pragma unroll
+  for (int k = 0; k < kJPass; ++k)
+    if (s0 + team + k * NT >= s1) al[k] = -1.f;
   load8(os + tl * 8, o);
   const float Z = os[kMaxD];
   const float invZ = Z > 0.f ? 1.f / Z : 0.f;
