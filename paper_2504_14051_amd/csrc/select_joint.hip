@@ -95,10 +95,8 @@ __device__ __forceinline__ float* record(const Params& p, int parity, int bh, in
 __device__ __forceinline__ Best head_winner(const Params& p, int parity, int bh) {
   const int lane = threadIdx.x & 63;
   Best v = {INFINITY, -1, 0.f};
-  if (lane < p.j_c) {
-    const float4 r = *reinterpret_cast<const float4*>(record(p, parity, bh, lane));
-    v.q = r.x; v.j = __float_as_int(r.y); v.w = r.z;
-  }
+  const float4 r = *reinterpret_cast<const float4*>(record(p, parity, bh, min(lane, p.j_c - 1)));
+  if (lane < p.j_c) { v.q = r.x; v.j = __float_as_int(r.y); v.w = r.z; }
   return wave_best(v);
 }
 
@@ -133,8 +131,12 @@ __global__ __launch_bounds__(kJT) void k_joint_step(const Params p, int32_t* ord
   if (t > 0) {
 #pragma unroll
     for (int i = 0; i < kJPre; ++i) {
-      const int idx = tid + i * kJT;
-      if (idx < p.j_c * F4) pre[i] = *reinterpret_cast<const float4*>(record(p, par ^ 1, bh, idx / F4) + 4 + (idx % F4) * 4);
+      // a workgroup-uniform bound, and inside it a clamped index instead of a lane-dependent
+      // condition: loads under one are waited for one by one
+      if (i * kJT < p.j_c * F4) {
+        const int idx = min(tid + i * kJT, p.j_c * F4 - 1);
+        pre[i] = *reinterpret_cast<const float4*>(record(p, par ^ 1, bh, idx / F4) + 4 + (idx % F4) * 4);
+      }
     }
     load8(p.j_u + head2p * kMaxD + tl * 8, u);
     rest_all = p.j_rest[head2p];
