@@ -458,6 +458,33 @@ def test_length_and_budget_edges(B, oracle, lens, budget):
     full_check(B, oracle, cache, budget)
 
 
+@pytest.mark.parametrize("lens,budget", [
+    ([700, 1], 200),        # a cache of one token
+    ([300, 0], 200),        # an empty sequence is skipped
+    ([201, 200], 200),      # evict exactly one / evict none
+    ([700, 2], 1),          # budget of one
+    ([700, 700], 699),      # evict one everywhere
+    ([512, 511], 100),
+])
+@pytest.mark.parametrize("mode", [0, 1], ids=["stable", "swap-last"])
+def test_length_and_budget_edges_one_query_row(B, oracle, lens, budget, mode):
+    """The same edges on the generation path (one query position per head: few-row key sweep,
+    register-resident value kernel, evict-one fast path in the selection)."""
+    wl = small(budget=budget, window=1)
+    lens = np.array(lens, dtype=np.int32)
+    cache = synth.make_cache(wl, seq_lens=np.maximum(lens, 1), base_init="random")
+    cache.seq_lens = torch.as_tensor(lens)
+    full_check(B, oracle, cache, budget, mode=mode)
+
+
+def test_all_rows_protected_and_single_scored_token_one_query_row(B, oracle):
+    for tail in (34, 33, 0):
+        wl = small(context=64, budget=40, window=1, n_protect_head=30, n_protect_tail=tail, batch=1)
+        full_check(B, oracle, synth.make_cache(wl), wl.budget)
+    wl = small(context=64, budget=63, window=1, n_protect_head=0, n_protect_tail=64, batch=1)
+    full_check(B, oracle, synth.make_cache(wl), wl.budget, mode=1)     # evict one, every row protected
+
+
 def test_all_rows_protected_and_single_scored_token(B, oracle):
     wl = small(context=64, budget=40, n_protect_head=30, n_protect_tail=34, batch=1)
     full_check(B, oracle, synth.make_cache(wl), wl.budget)
