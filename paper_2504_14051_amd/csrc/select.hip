@@ -414,6 +414,32 @@ __device__ __forceinline__ void swap_last_row(const Params& p, int bh, int b, in
     p.base[(int64_t)bh * p.cap + hole] = (p.combine_in_select ? p.h : p.base)[(int64_t)bh * p.cap + N - 1];
 }
 
+// One token leaves (generation): the smallest key goes, among equal keys the highest index;
+// no histogram, one reduction.  `best` packs a thread's candidates, key in the high word and
+// ~index in the low word (the minimum over the head is the token to drop).  Writes the kept
+// list and, in the fused call in swap-last mode, moves the last row into the hole.
+__device__ __forceinline__ void evict_one(const Params& p, unsigned long long best, int bh, int b, int hk,
+                                          int N, int row_bytes, unsigned long long* wave_min) {
+  const int tid = threadIdx.x, k = p.budget;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const unsigned long long c = __shfl_xor(best, o, kWave);
+    best = c < best ? c : best;
+  }
+  if ((tid & 63) == 0) wave_min[tid >> 6] = best;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kSW; ++w) best = wave_min[w] < best ? wave_min[w] : best;
+  const int hole = (int)~(uint32_t)best;
+  int32_t* out = p.kept + (int64_t)bh * k;
+  for (int i = tid; i < k; i += kST) out[i] = i < hole ? i : i + 1;
+  if (p.select_swaps && p.mode == CAOTE_COMPACT_SWAP_LAST && hole != N - 1)
+    swap_last_row(p, bh, b, hk, hole, N, row_bytes);
+}
+__device__ __forceinline__ unsigned long long pack_candidate(uint32_t key, int j) {
+  return ((unsigned long long)key << 32) | (uint32_t)~(uint32_t)j;
+}
+
 // The score of token j: from memory or, in the fused call on a short cache, put together here
 // from the column slices that k_vside left (and written out on the way).
 __device__ __forceinline__ float score_at(const Params& p, const float* sc, int bh, int j, int N) {
@@ -447,30 +473,13 @@ __global__ __launch_bounds__(kST) void k_select_small(const Params p, int row_by
     valid[e] = j0 + e < N;
     key[e] = valid[e] ? float_key(score_at(p, sc, bh, j0 + e, N)) : 0u;
   }
-  // ---- one token leaves (generation): the smallest key goes, among equal keys the highest
-  // index; no histogram, one reduction ----------------------------------------------------
-  if (N - k == 1) {
+  if (N - k == 1) {                       // one token leaves: no histogram
     __shared__ unsigned long long wave_min[kSW];
-    unsigned long long best = ~0ull;      // key in the high word, ~index in the low word
+    unsigned long long best = ~0ull;
 #pragma unroll
     for (int e = 0; e < kSPer; ++e)
-      if (valid[e]) {
-        const unsigned long long c = ((unsigned long long)key[e] << 32) | (uint32_t)~(uint32_t)(j0 + e);
-        best = c < best ? c : best;
-      }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-      const unsigned long long c = __shfl_xor(best, o, kWave);
-      best = c < best ? c : best;
-    }
-    if ((tid & 63) == 0) wave_min[tid >> 6] = best;
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < kSW; ++w) best = wave_min[w] < best ? wave_min[w] : best;
-    const int hole = (int)~(uint32_t)best;
-    for (int i = tid; i < k; i += kST) out[i] = i < hole ? i : i + 1;
-    if (p.select_swaps && p.mode == CAOTE_COMPACT_SWAP_LAST && hole != N - 1)
-      swap_last_row(p, bh, b, hk, hole, N, row_bytes);
+      if (valid[e]) { const unsigned long long c = pack_candidate(key[e], j0 + e); best = c < best ? c : best; }
+    evict_one(p, best, bh, b, hk, N, row_bytes, wave_min);
     return;
   }
 #pragma unroll
@@ -603,6 +612,19 @@ __global__ __launch_bounds__(kST) void k_select_one(const Params p, int row_byte
       const int j = u * kSmallCap + tid * kSPer + e;
       key[u][e] = j < N ? float_key(score_at(p, sc, bh, j, N)) : 0u;
     }
+  if (N - k == 1) {                       // one token leaves: no histogram
+    __shared__ unsigned long long wave_min[kSW];
+    unsigned long long best = ~0ull;
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int e = 0; e < kSPer; ++e) {
+        const int j = u * kSmallCap + tid * kSPer + e;
+        if (j < N) { const unsigned long long c = pack_candidate(key[u][e], j); best = c < best ? c : best; }
+      }
+    evict_one(p, best, bh, b, hk, N, row_bytes, wave_min);
+    return;
+  }
 #pragma unroll
   for (int u = 0; u < kHistBins / kST; ++u) hist[tid + u * kST] = 0;
   if (tid == 0) s_hole = -1;

@@ -532,7 +532,7 @@ def _layout_only(B, batch, hkv, cap, d=128, dtype=torch.bfloat16):
 
 
 @pytest.mark.parametrize("cap,budget", [(1, 1), (63, 10), (1000, 999), (2049, 2048), (4096, 100), (4096, 4095),
-                                        (4097, 2048), (5000, 1234), (8192, 8191), (12345, 6000), (16384, 3), (16385, 8000), (20000, 100), (32768, 2048),
+                                        (4097, 2048), (4097, 4096), (5000, 1234), (8192, 8191), (8193, 8192), (16384, 16383), (12345, 6000), (16384, 3), (16385, 8000), (20000, 100), (32768, 2048),
                                         (32769, 2048), (40000, 2048), (131072, 4096),
                                         (300000, 100000)])
 def test_select_exact_with_ties_and_infinities(B, oracle, cap, budget):
