@@ -1,5 +1,6 @@
 // C ABI of the CAOTE hot path: argument validation, workspace carving, launches.
 // No allocation, no synchronisation, no state between calls.
+#include <algorithm>
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
@@ -103,6 +104,18 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   else
     p.split_len = chunk_len(1024, 256, 8192);
   p.n_split = ceil_div(p.cap, p.split_len);
+  p.split_len0 = p.split_len; p.n_split0 = p.n_split; p.n_rg0 = 1;
+  if (p.use_mfma) {
+    // rows a workgroup of the matrix-core sweeps keeps in registers (see launch_score_mfma)
+    const int nrb = ceil_div(p.R, 32), rows = nrb <= 2 ? 64 : (nrb <= 4 ? 128 : 256);
+    const int n_rg = ceil_div(p.R, rows);
+    if (n_rg > 1) {      // several row groups: side by side in the first sweep instead of in turn
+      const int want = std::max(1, (rows == 256 ? 256 : 512) / (BH * n_rg));
+      p.split_len0 = std::max(128, (int)align_up((size_t)ceil_div(p.cap, want), 64));
+      p.n_split0 = ceil_div(p.cap, p.split_len0);
+      p.n_rg0 = n_rg;
+    }
+  }
   p.vchunk_len = caote::kVChunk;
   p.n_vchunk = ceil_div(p.cap, p.vchunk_len);
   p.vrep = ceil_div(p.cap, 128 * caote::kVChunk);      // at most 128 partial sums per head
@@ -119,7 +132,7 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
 
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return ws ? ws + o : nullptr; };
-  p.stats = (float*)carve((size_t)BH * p.n_split * p.Rp * 2 * sizeof(float));
+  p.stats = (float*)carve((size_t)BH * std::max(p.n_split, p.n_split0) * p.Rp * 2 * sizeof(float));
   p.lse2 = (float*)carve((size_t)BH * p.Rp * sizeof(float));
   p.S = (float*)carve(p.small_r ? (size_t)BH * p.s_pitch * p.s_rows * sizeof(float) : 0);
   p.a = (float*)carve((size_t)BH * p.cap * sizeof(float));

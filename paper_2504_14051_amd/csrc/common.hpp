@@ -60,6 +60,9 @@ struct Params {
   double* j_rest;     // [2][BH]                 1 - evicted weight, by step parity
   int j_c, j_slice;   // slices per head, tokens per slice
   int n_split, split_len, Rp, n_vchunk, vchunk_len;
+  // the first key sweep and the merge of its row statistics: the same split unless the
+  // matrix-core sweep has several row groups, which then go into the grid with longer splits
+  int n_split0, split_len0, n_rg0;
   int vrep, n_vsum;   // value sum: 256-token chunks per workgroup, partial sums per head
   int use_mfma;       // key sweeps on the matrix cores (bf16, head_dim 128, R > 16)
   int halo;           // SnapKV: pooling half-width (0 otherwise)
@@ -144,8 +147,8 @@ __device__ __forceinline__ float row_lse2(const Params& p, int b, int hk, int bh
 // log2-domain normaliser of query row r from the partial (max, sum) pairs that the first key
 // sweep left per split: lse2_r = log2 sum_j exp2(t_rj).
 __device__ __forceinline__ float merged_lse2(const Params& p, int bh, int r, int N) {
-  const int ns = (N + p.split_len - 1) / p.split_len;
-  const float* st = p.stats + ((int64_t)bh * p.n_split * p.Rp + r) * 2;
+  const int ns = (N + p.split_len0 - 1) / p.split_len0;
+  const float* st = p.stats + ((int64_t)bh * p.n_split0 * p.Rp + r) * 2;
   float M = -INFINITY;
   for (int s = 0; s < ns; ++s) M = fmaxf(M, st[(int64_t)s * p.Rp * 2]);
   float L = 0.f;

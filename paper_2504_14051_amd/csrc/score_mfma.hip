@@ -68,12 +68,14 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   constexpr bool QLDS = NWV == 8;
   const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
-  const int c0 = blockIdx.x * p.split_len;
+  // the first sweep may have its own split, with the row groups spread over the grid
+  const int split_len = MODE == 0 ? p.split_len0 : p.split_len;
+  const int c0 = blockIdx.x * split_len;
   // with the caller's normalisers this is the first kernel of the call: it clears the
   // selection's counters (otherwise the merge of the row statistics does)
   if (COLSUM && p.lse_in && blockIdx.x == 0) reset_counters(p, bh);
   if (c0 >= N) return;
-  const int c1 = min(N, c0 + p.split_len);
+  const int c1 = min(N, c0 + split_len);
   const int ntiles = (c1 - c0 + kTN - 1) / kTN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / WK, kw = wave % WK;
@@ -97,7 +99,8 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   const int64_t krow = p.ksn * 2;
   float* a_out = p.a + (int64_t)bh * p.cap;
 
-  for (int rg0 = 0; rg0 < p.R; rg0 += ROWS) {
+  const int rg_first = MODE == 0 ? blockIdx.z * ROWS : 0, rg_step = MODE == 0 ? gridDim.z * ROWS : ROWS;
+  for (int rg0 = rg_first; rg0 < p.R; rg0 += rg_step) {
     // ---- sweep over the key tiles of this split --------------------------------------
     // K tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane L of
     // a wave fills the 16-byte slot base + 16 L), kNBuf-1 tiles ahead of the math.  The
@@ -455,7 +458,7 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
 #pragma unroll
         for (int w = 0; w < WK; ++w)
           if (st_lds[w][rl][0] > -INFINITY) L += st_lds[w][rl][1] * exp2f(st_lds[w][rl][0] - M);
-        float* st = p.stats + (((int64_t)bh * p.n_split + blockIdx.x) * p.Rp + rg0 + rl) * 2;
+        float* st = p.stats + (((int64_t)bh * p.n_split0 + blockIdx.x) * p.Rp + rg0 + rl) * 2;
         st[0] = M; st[1] = L;
       }
     }
@@ -471,8 +474,8 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_stats_wave(const Params
   const int lane = threadIdx.x & 63;
   if (r >= p.R) return;
   const int N = seq_len(p, b);
-  const int ns = (N + p.split_len - 1) / p.split_len;
-  const float* st = p.stats + ((int64_t)bh * p.n_split * p.Rp + r) * 2;
+  const int ns = (N + p.split_len0 - 1) / p.split_len0;
+  const float* st = p.stats + ((int64_t)bh * p.n_split0 * p.Rp + r) * 2;
   float M = -INFINITY;
   for (int s = lane; s < ns; s += kWave) M = fmaxf(M, st[(int64_t)s * p.Rp * 2]);
 #pragma unroll
@@ -650,7 +653,8 @@ template <int NWV, int WR, int RBW>
 hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_split, p.B * p.Hkv);
   if (!p.lse_in) {                       // else the caller's attention pass has done sweep 1
-    hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid, dim3(NWV * kWave), 0, s, p);
+    const dim3 grid0(p.n_split0, p.B * p.Hkv, p.n_rg0);
+    hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid0, dim3(NWV * kWave), 0, s, p);
     mark(hook, "key_rowstats");
     if (launch_merge_stats(p, s, hook) != hipSuccess) return hipGetLastError();
   }
