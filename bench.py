@@ -114,6 +114,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama3-8b-32k")
     ap.add_argument("--layers", type=int, default=16, help="independent layer buffers to rotate over")
+    ap.add_argument("--batch", type=int, default=0, help="sequences per call (default: the workload's own)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--calls-in-flight", type=int, default=4,
@@ -135,6 +136,8 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]()
+    if args.batch > 0:
+        wl = wl.with_(batch=args.batch)
     host = synth.make_cache(wl)
     n_layers = max(1, args.layers)
     mode = B.COMPACT_SWAP_LAST if swap_last(wl) else B.COMPACT_STABLE
