@@ -492,9 +492,11 @@ def test_all_rows_protected_and_single_scored_token(B, oracle):
     full_check(B, oracle, synth.make_cache(wl), wl.budget)
 
 
-def test_strided_views(B, oracle):
-    """K and V as slices of a larger allocation (row stride > head_dim)."""
-    wl = small(batch=1)
+@pytest.mark.parametrize("window", [8, 1], ids=["window8", "one-query-row"])
+def test_strided_views(B, oracle, window):
+    """K and V as slices of a larger allocation (row stride > head_dim), on the prefill and on
+    the generation path."""
+    wl = small(batch=1, window=window)
     cache = synth.make_cache(wl)
     padK = torch.zeros(1, 2, wl.context, 256, dtype=cache.K.dtype)
     padV = torch.zeros(1, 2, wl.context, 256, dtype=cache.K.dtype)
