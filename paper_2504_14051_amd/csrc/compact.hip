@@ -37,11 +37,23 @@ __global__ __launch_bounds__(kThreads) void k_swap_last(const Params p, int row_
   const int n_keep = min(N, p.budget);
   if (N - n_keep != 1) return;
   const int32_t* idx = p.kept + (int64_t)bh * p.budget;
-  __shared__ int s_hole;
-  if (threadIdx.x == 0) s_hole = N - 1;                 // nothing missing below: the last row goes
+  // The hole is the first rank whose index is not its own; ranks below it hold their own index,
+  // ranks from it on hold index + 1, so two rounds of loads find it: the segment (one probe per
+  // thread, at the end of its segment), then the rank inside the segment.
+  __shared__ int s_seg, s_hole;
+  if (threadIdx.x == 0) { s_seg = kThreads; s_hole = N - 1; }   // nothing missing: the last row goes
   __syncthreads();
-  for (int i = threadIdx.x; i < n_keep; i += kThreads)  // the first rank whose index is not its own
-    if (idx[i] != i && (i == 0 || idx[i - 1] == i - 1)) s_hole = i;
+  const int seg = (n_keep + kThreads - 1) / kThreads;
+  {
+    const int e = min(n_keep, (threadIdx.x + 1) * seg) - 1;     // last rank of this thread's segment
+    if (threadIdx.x * seg < n_keep && idx[e] != e) atomicMin(&s_seg, (int)threadIdx.x);
+  }
+  __syncthreads();
+  if (s_seg < kThreads) {
+    const int i0 = s_seg * seg, i1 = min(n_keep, i0 + seg);
+    for (int i = i0 + threadIdx.x; i < i1; i += kThreads)
+      if (idx[i] != i) atomicMin(&s_hole, i);
+  }
   __syncthreads();
   const int hole = s_hole;
   if (hole == N - 1) return;

@@ -406,20 +406,22 @@ def test_sharp_and_flat_softmax(B, oracle, kw, factor):
 
 
 @pytest.mark.parametrize("kw", [
-    dict(window=1, context=2176, budget=2100),                          # two column workgroups, full
-    dict(window=1, context=2177, budget=2000),                          # four
-    dict(window=2, context=4352, budget=4000, batch=1),                 # four, full
-    dict(window=1, context=5000, budget=4999, batch=1),                 # eight
+    dict(window=1, context=2176, budget=2100),                          # register-resident value rows, full
+    dict(window=1, context=2177, budget=2000),                          # one row more: the streaming value kernels
+    dict(window=2, context=4352, budget=4000, batch=1),
+    dict(window=1, context=5000, budget=4999, batch=1),
     dict(window=1, context=8704, budget=8000, batch=1, base=synth.BASE_NONE),
-    dict(window=1, context=8705, budget=8000, batch=1),                 # beyond: the streaming value kernels
+    dict(window=1, context=8705, budget=8000, batch=1),
     dict(window=4, context=3000, budget=2500, batch=1),                 # 16 query rows: two vector-ALU key sweeps
     dict(window=4, context=3000, budget=2500, batch=1, base=synth.BASE_SNAPKV, pool_kernel=9, n_protect_tail=4),
     dict(window=1, context=2500, budget=2400, base=synth.BASE_SNAPKV, pool_kernel=301, n_protect_head=3),
-], ids=["cs2-full", "cs4", "cs4-full", "cs8", "cs8-full", "streaming", "generic-h2o", "generic-snapkv", "wide-pool"])
+], ids=["resident-full", "streaming-2177", "streaming-4352", "streaming-5000", "streaming-8704", "streaming-8705",
+        "generic-h2o", "generic-snapkv", "wide-pool"])
 @pytest.mark.parametrize("variant", [0, 1], ids=["exact", "fast"])
 def test_value_side_column_splits(B, oracle, kw, variant):
-    """Short caches keep a head's value rows in registers, a head cut by columns into 2, 4 or
-    8 workgroups: every split at its size limits, both variants, every base mode."""
+    """Short caches keep a head's value rows in registers (a head cut by columns into two
+    workgroups), longer ones stream V twice: both sides of the limit, both variants, every
+    base mode."""
     wl = small(**kw)
     lens = None
     if wl.batch > 1:
@@ -581,6 +583,28 @@ def test_compact_hazard_patterns(B, oracle, pattern, dtype, d):
     torch.cuda.synchronize()
     cache = synth.Cache(None, None, K, V, base, None)
     H.check_compaction(oracle, K, V, base, dK.cpu(), dV.cpu(), db.cpu(), kept.numpy(), cache, budget)
+
+
+@pytest.mark.parametrize("cap", [2, 257, 5000, 20000])
+def test_swap_last_finds_the_hole(B, oracle, cap):
+    """caote_compact in swap-last mode on evict-one kept lists: the hole at the first rank, inside
+    and at the ends of the search segments, at the last kept rank, and the last row itself evicted."""
+    budget, d, dtype = cap - 1, 128, torch.bfloat16
+    seg = (budget + 255) // 256
+    holes = sorted({0, min(seg - 1, cap - 1), min(seg, cap - 1), cap // 2, max(cap - 2, 0), cap - 1})
+    g = torch.Generator().manual_seed(cap)
+    K = torch.randn(len(holes), 1, cap, d, generator=g).to(dtype)
+    V = torch.randn(len(holes), 1, cap, d, generator=g).to(dtype)
+    base = torch.rand(len(holes), 1, cap, generator=g)
+    kept = np.stack([np.delete(np.arange(cap, dtype=np.int32), h) for h in holes])[:, None, :]
+    dK, dV, db = K.cuda(), V.cuda(), base.cuda()
+    L = B.make_layout(torch.empty(len(holes), 1, 1, d, dtype=dtype, device="cuda"), dK, dV, base=B.BASE_NONE,
+                      softmax_scale=1.0)
+    ws = torch.empty(B.caote_workspace_bytes(L, budget), dtype=torch.uint8, device="cuda")
+    B.caote_compact(dK, dV, db, torch.from_numpy(kept).cuda(), L, budget, B.COMPACT_SWAP_LAST, ws)
+    torch.cuda.synchronize()
+    cache = synth.Cache(None, None, K, V, base, None)
+    H.check_compaction(oracle, K, V, base, dK.cpu(), dV.cpu(), db.cpu(), kept, cache, budget, "swap_last")
 
 
 def test_hip_graph_replays_match_eager(B):
