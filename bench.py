@@ -233,7 +233,7 @@ def main():
 
     def timed_replay(step_fn, n_again=0):
         """K steps captured once into a HIP graph (the library neither allocates nor
-        synchronises; eager launches are launch-bound: six to nine short kernels per step)."""
+        synchronises; eager launches are launch-bound: three to nine short kernels per step)."""
         nonlocal stream
         outer = stream
         side = torch.cuda.Stream()
