@@ -656,7 +656,8 @@ hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
     const dim3 grid0(p.n_split0, p.B * p.Hkv, p.n_rg0);
     hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid0, dim3(NWV * kWave), 0, s, p);
     mark(hook, "key_rowstats");
-    if (launch_merge_stats(p, s, hook) != hipSuccess) return hipGetLastError();
+    const hipError_t e = launch_merge_stats(p, s, hook);
+    if (e != hipSuccess) return e;
   }
   if (p.fuse_v) hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 2>), grid, dim3(NWV * kWave), 0, s, p);
   else          hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 1>), grid, dim3(NWV * kWave), 0, s, p);

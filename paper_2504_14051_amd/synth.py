@@ -171,3 +171,23 @@ def make_cache(wl: Workload, seq_lens=None, layer: int = 0, base_init: str = "ze
         base=torch.from_numpy(base),
         seq_lens=None if seq_lens is None else torch.as_tensor(np.asarray(seq_lens), dtype=torch.int32),
     )
+
+
+def decode_append(wl: Workload, step: int, layer: int = 0):
+    """What one generation step brings: a fresh query position per head and one new (k, v) row
+    per (sequence, KV head), with the statistics of `make_cache` (queries share the group's
+    component mu_g of sequence b, which stays the same over the steps; log-normal value norm).
+    Returns (q [B,Hq,1,d], k_new [B,Hkv,1,d], v_new [B,Hkv,1,d]) in the storage dtype."""
+    B, Hq, Hkv, d, G = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.group
+    q = np.empty((B, Hq, 1, d), dtype=np.float32)
+    k = np.empty((B, Hkv, 1, d), dtype=np.float32)
+    v = np.empty((B, Hkv, 1, d), dtype=np.float32)
+    for b in range(B):
+        mu = _rng(wl.seed, 4, b, layer).standard_normal((Hkv, 1, 1, d), dtype=np.float32)
+        r = _rng(wl.seed, 5, b * 65536 + step, layer)
+        q[b] = (r.standard_normal((Hkv, G, 1, d), dtype=np.float32) + mu).reshape(Hq, 1, d)
+        k[b] = r.standard_normal((Hkv, 1, d), dtype=np.float32)
+        v[b] = r.standard_normal((Hkv, 1, d), dtype=np.float32) * np.exp(
+            0.5 * r.standard_normal((Hkv, 1, 1), dtype=np.float32))
+    dt = wl.torch_dtype
+    return torch.from_numpy(q).to(dt), torch.from_numpy(k).to(dt), torch.from_numpy(v).to(dt)

@@ -79,6 +79,10 @@ def full_check(B, oracle, cache, budget, mode=0, variant=0, row_lse=None):
         for key in ("K_after", "V_after"):
             assert torch.equal(res[key][b, :, :n_keep].view(torch.int16 if wl.dtype == "bf16" else torch.int32),
                                fz[key][b, :, :n_keep].view(torch.int16 if wl.dtype == "bf16" else torch.int32))
+        if wl.base == synth.BASE_H2O:    # the fused call moves the accumulator in code of its own
+            assert torch.equal(res["base_after"][b, :, :n_keep].view(torch.int32),
+                               fz["base_after"][b, :, :n_keep].view(torch.int32)), \
+                "caote_evict differs in the compacted accumulator"
     return worst
 
 
@@ -194,8 +198,77 @@ def test_blockwise_prefill_stream(B, oracle):
             ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
             scores = torch.empty(wl.batch, wl.n_kv_heads, wl.context, device="cuda")
             kept = torch.empty(wl.batch, wl.n_kv_heads, wl.budget, dtype=torch.int32, device="cuda")
+        base_in = host.base.clone()
         B.caote_evict(dev.q, dev.K, dev.V, dev.base, L, wl.budget, 0, scores, kept, ws)
         torch.cuda.synchronize()
+        # the state that the next block starts from: the accumulator h = h_in + a of the kept
+        # rows (oracle), moved to the front as the GPU's own kept list says
+        _, oh, _ = H.oracle_scores(oracle, host)
+        kept_h = kept.cpu().numpy()
+        got = dev.base.cpu()
+        for b in range(wl.batch):
+            for hk in range(wl.n_kv_heads):
+                ref = oh[b, hk][kept_h[b, hk]]
+                np.testing.assert_allclose(got[b, hk, :wl.budget].numpy(), ref, rtol=H.RTOL[wl.dtype], atol=1e-7)
+        assert torch.equal(base_in, host.base)
+
+
+# ---- configs[4] at its stated size: ragged batch-16 prefill eviction, then the decode stream ----
+
+def test_cfg5_ragged_prefill_eviction_batch16_at_size(B, oracle):
+    """The set-up of the decode stream as the workload states it: 16 sequences with prefill
+    lengths uniform in 8k..32k, each cut to the budget of 2048 per KV head in ONE call with
+    seq_lens (SnapKV base, window 64, pool 7): BH = 128, so the planner's key splits are the
+    ones the benchmark's ragged call runs with, not those of a single layer."""
+    wl = synth.llama3_8b_32k().with_(batch=16, name="llama3-8b-prefill-ragged16")
+    lens = synth.prefill_lengths(wl.seed, wl.batch)
+    assert lens.min() >= 8192 and lens.max() <= 32768 and len(set(lens.tolist())) > 8
+    cache = synth.make_cache(wl, seq_lens=lens)
+    full_check(B, oracle, cache, wl.budget)
+
+
+def test_cfg5_decode_stream_batch16_256_steps(B, oracle):
+    """The stream itself at the stated batch: 16 caches of 2048 + 1 rows per KV head, one query
+    position per head, H2O accumulator carried, evict one per head, last row into the hole;
+    256 steps on each of 2 layers.  The GPU runs all 16 sequences (BH = 128: the timed
+    geometry); the oracle follows sequences 0 and 1, restarted from the GPU's own state at
+    every step, and checks scores, accumulator, kept lists and the moved rows."""
+    wl = synth.decode_step(batch=16)
+    sub = wl.with_(batch=2)
+    rtol = H.RTOL[wl.dtype]
+    n_steps = 256
+    for layer in range(2):
+        dev = H.to_device(synth.make_cache(wl, layer=layer, base_init="random"))
+        L = B.layout_for(wl, dev)
+        ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
+        scores = torch.empty(wl.batch, wl.n_kv_heads, wl.context, device="cuda")
+        kept = torch.empty(wl.batch, wl.n_kv_heads, wl.budget, dtype=torch.int32, device="cuda")
+        q = dev.q
+        worst = 0.0
+        for step in range(n_steps):
+            before = synth.Cache(sub, q[:2].cpu(), dev.K[:2].cpu(), dev.V[:2].cpu(), dev.base[:2].cpu(), None)
+            Lq = B.make_layout(q, dev.K, dev.V, base=wl.base, softmax_scale=wl.softmax_scale)
+            B.caote_evict(q, dev.K, dev.V, dev.base, Lq, wl.budget, B.COMPACT_SWAP_LAST, scores, kept, ws)
+            torch.cuda.synchronize()
+            oc, oh, _ = H.oracle_scores(oracle, before, threads=16)
+            sc, kp = scores[:2].cpu().numpy(), kept[:2].cpu().numpy()
+            worst = max(worst, H.check_scores(sc, oc, oh, before, rtol))
+            H.check_kept(kp, oc, before, wl.budget, rtol, gpu_scores=sc)
+            # the accumulator after the step: h of every kept row, the last row in the hole
+            got_base = dev.base[:2].cpu()
+            K_after, V_after = dev.K[:2].cpu(), dev.V[:2].cpu()
+            for b in range(2):
+                for hk in range(wl.n_kv_heads):
+                    ref, _ = oracle.compact_one(oh[b, hk], kp[b, hk], "swap_last")
+                    np.testing.assert_allclose(got_base[b, hk, :wl.budget].numpy(), ref[:wl.budget],
+                                               rtol=rtol, atol=1e-7)
+            H.check_compaction(oracle, before.K, before.V, None, K_after, V_after, None, kp, before,
+                               wl.budget, "swap_last")
+            # the next token joins every cache
+            q_h, k_new, v_new = synth.decode_append(wl, step, layer)
+            q = q_h.cuda()
+            B.caote_append(dev.K, dev.V, dev.base, k_new.cuda(), v_new.cuda(), L, wl.budget, 1)
+        assert worst < rtol
 
 
 # ---- shapes, modes, edges -------------------------------------------------------------
