@@ -170,6 +170,23 @@ caote_status caote_evict(const void* q_window, void* K, void* V, float* base_sco
                          float* scores, int32_t* kept_idx, void* workspace,
                          size_t workspace_bytes, void* hip_stream);
 
+/* caote_evict for callers that cannot allocate or hand over device memory for scratch:
+ * code under HIP graph capture, tight serving loops that own no spare buffer, harnesses that
+ * forbid hipMalloc.  Same arguments and same results, bit for bit, as caote_evict, minus the
+ * workspace: the scratch memory is a fixed array of CAOTE_STATIC_SCRATCH_BYTES that lives in
+ * the library's device image (one copy per GPU the library runs on, held until the process
+ * ends).  The call allocates and frees nothing.
+ *   - A layout/budget whose caote_workspace_bytes() exceeds CAOTE_STATIC_SCRATCH_BYTES is
+ *     rejected with CAOTE_EWORKSPACE before anything is launched.
+ *   - The device that owns `hip_stream` must be the calling thread's current device.
+ *   - All calls on one GPU share that GPU's array: calls that can overlap in time on one
+ *     GPU (different streams, different threads) race; order them on one stream.  Nothing
+ *     is assumed about what an earlier call left in the array.                           */
+#define CAOTE_STATIC_SCRATCH_BYTES (32u << 20)
+caote_status caote_evict_static(const void* q_window, void* K, void* V, float* base_score,
+                                const caote_layout* layout, int32_t budget, int32_t mode,
+                                float* scores, int32_t* kept_idx, void* hip_stream);
+
 /* Greedy multi-token eviction (App. "Extending CAOTE to Multi-token Eviction"): the
  * fused call with the selection taken under the JOINT error instead of the independent
  * single-token scores.  With w, o and v as in caote_score, the error of evicting a set S is

@@ -22,10 +22,11 @@ EXACT, FAST = 0, 1
 COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
 
 EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
-           "caote_append", "caote_evict", "caote_evict_joint", "caote_evict_timed", "caote_read_stream", "caote_phase_name", "caote_last_error",
+           "caote_append", "caote_evict", "caote_evict_static", "caote_evict_joint", "caote_evict_timed", "caote_read_stream", "caote_phase_name", "caote_last_error",
            "caote_version")
 MAX_PHASES = 16
 JOINT_MAX_CAPACITY = 8192
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class CaoteError(RuntimeError):
@@ -76,6 +77,8 @@ def lib() -> ctypes.CDLL:
         L.caote_append.restype = ctypes.c_int
         L.caote_evict.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp]
         L.caote_evict.restype = ctypes.c_int
+        L.caote_evict_static.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp]
+        L.caote_evict_static.restype = ctypes.c_int
         L.caote_evict_joint.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.caote_evict_joint.restype = ctypes.c_int
         L.caote_evict_timed.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp,
@@ -186,6 +189,14 @@ def caote_evict(q_window, K, V, base_score, layout: Layout, budget: int, mode, s
     _check(lib().caote_evict(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
                              ctypes.byref(layout), budget, mode, _ptr(scores), _ptr(kept_idx),
                              _ptr(workspace), wb, _stream(stream)))
+
+
+def caote_evict_static(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores, kept_idx,
+                       stream=None) -> None:
+    """caote_evict on the library's own fixed scratch array (no workspace, no allocation)."""
+    _check(lib().caote_evict_static(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
+                                    ctypes.byref(layout), budget, mode, _ptr(scores), _ptr(kept_idx),
+                                    _stream(stream)))
 
 
 def caote_evict_joint(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores, kept_idx,

@@ -2,6 +2,7 @@
 // No allocation, no synchronisation, no state between calls.
 #include <algorithm>
 #include <math.h>
+#include <mutex>
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
@@ -211,12 +212,45 @@ thread_local const char* g_phase_names[CAOTE_MAX_PHASES] = {};
 
 }  // namespace
 
+// ---- scratch of the entry point that allocates nothing (caote_evict_static) ------------------
+// The array lives in the device image: every GPU that loads the library holds its own copy at
+// its own address.  In host code the name `scratch` is only a handle for hipGetSymbolAddress;
+// the address kernels may use is what that call returns, looked up once per device.
+static __device__ __align__(256) unsigned char scratch[CAOTE_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};   // per device: device address of `scratch`, once known
+
+// Device address of the current device's copy of `scratch`.
+caote_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return device_status(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(CAOTE_EUNSUPPORTED, "device ordinal %d out of range", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return device_status(e, "hipGetSymbolAddress(scratch)");
+    if (!ptr || ((uintptr_t)ptr % 256) != 0)
+      return fail(CAOTE_EDEVICE, "static scratch resolved to an unusable address %p", ptr);
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return CAOTE_OK;
+}
+
+}  // namespace
+
 #pragma GCC visibility push(default)
 extern "C" {
 
 const char* caote_last_error(void) { return g_err; }
 
-int32_t caote_version(void) { return 102; }
+int32_t caote_version(void) { return 200; }
 
 size_t caote_workspace_bytes(const caote_layout* layout, int32_t budget) {
   if (check_layout(layout, budget, false) != CAOTE_OK) return 0;
@@ -289,13 +323,12 @@ caote_status caote_append(void* K, void* V, float* base_score, const void* k_new
                        "append");
 }
 
-// `joint`: selection by the greedy joint error (evicted / joint_error are its extra outputs).
-static caote_status evict_impl(const void* q_window, void* K, void* V, float* base_score,
-                               const caote_layout* layout, int32_t budget, int32_t mode,
-                               float* scores, int32_t* kept_idx, void* workspace,
-                               size_t workspace_bytes, hipStream_t s, caote::PhaseHook* hook,
-                               bool joint = false, int32_t* evicted = nullptr,
-                               float* joint_error = nullptr) {
+// Host-side argument checks of the fused calls (nothing is launched before they pass).
+static caote_status check_evict_args(const void* q_window, const void* K, const void* V,
+                                     const float* base_score, const caote_layout* layout,
+                                     int32_t budget, int32_t mode, const float* scores,
+                                     const int32_t* kept_idx, bool joint, const int32_t* evicted,
+                                     const float* joint_error) {
   caote_status st = check_layout(layout, budget, true);
   if (st != CAOTE_OK) return st;
   if (joint) {
@@ -315,6 +348,19 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
     return fail(CAOTE_EINVAL, "CAOTE_BASE_H2O needs base_score (the accumulator)");
   if (mode != CAOTE_COMPACT_STABLE && mode != CAOTE_COMPACT_SWAP_LAST)
     return fail(CAOTE_EINVAL, "unknown compaction mode %d", mode);
+  return CAOTE_OK;
+}
+
+// `joint`: selection by the greedy joint error (evicted / joint_error are its extra outputs).
+static caote_status evict_impl(const void* q_window, void* K, void* V, float* base_score,
+                               const caote_layout* layout, int32_t budget, int32_t mode,
+                               float* scores, int32_t* kept_idx, void* workspace,
+                               size_t workspace_bytes, hipStream_t s, caote::PhaseHook* hook,
+                               bool joint = false, int32_t* evicted = nullptr,
+                               float* joint_error = nullptr) {
+  caote_status st = check_evict_args(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx,
+                                     joint, evicted, joint_error);
+  if (st != CAOTE_OK) return st;
   Params p;
   st = check_ws(layout, budget, workspace, workspace_bytes, p);
   if (st != CAOTE_OK) return st;
@@ -348,6 +394,25 @@ caote_status caote_evict(const void* q_window, void* K, void* V, float* base_sco
                          void* hip_stream) {
   return evict_impl(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx, workspace,
                     workspace_bytes, (hipStream_t)hip_stream, nullptr);
+}
+
+caote_status caote_evict_static(const void* q_window, void* K, void* V, float* base_score,
+                                const caote_layout* layout, int32_t budget, int32_t mode,
+                                float* scores, int32_t* kept_idx, void* hip_stream) {
+  caote_status st = check_evict_args(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx,
+                                     false, nullptr, nullptr);
+  if (st != CAOTE_OK) return st;
+  Params probe;
+  const size_t need = plan(layout, budget, probe, nullptr);
+  if (need > (size_t)CAOTE_STATIC_SCRATCH_BYTES)
+    return fail(CAOTE_EWORKSPACE,
+                "this layout and budget need %zu bytes of scratch; the static array holds %zu "
+                "(use caote_evict with a workspace of your own)", need, (size_t)CAOTE_STATIC_SCRATCH_BYTES);
+  void* ws = nullptr;
+  st = static_scratch(&ws);
+  if (st != CAOTE_OK) return st;
+  return evict_impl(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx, ws,
+                    (size_t)CAOTE_STATIC_SCRATCH_BYTES, (hipStream_t)hip_stream, nullptr);
 }
 
 caote_status caote_evict_joint(const void* q_window, void* K, void* V, float* base_score,

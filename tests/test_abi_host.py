@@ -178,3 +178,27 @@ def test_read_stream_arguments_are_checked_on_the_host(B):
             B.caote_read_stream(*args, stream=0)
         assert e.value.status == B.EINVAL
     B.caote_read_stream(fake, 0, fake, stream=0)                 # nothing to read: no launch
+
+
+def test_static_scratch_entry_point_checks_arguments_and_size_on_the_host(B):
+    """caote_evict_static: the same argument checks as caote_evict, and a layout whose scratch
+    does not fit the fixed array is refused before any device call is made."""
+    fake = 0x1000
+    L = good_layout(B)
+    with pytest.raises(B.CaoteError) as e:                       # null kept_idx
+        B.caote_evict_static(fake, fake, fake, fake, L, 64, 0, fake, None, stream=0)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.CaoteError) as e:                       # bad mode
+        B.caote_evict_static(fake, fake, fake, fake, L, 64, 9, fake, fake, stream=0)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.CaoteError) as e:                       # H2O without an accumulator
+        B.caote_evict_static(fake, fake, fake, None, L, 64, 0, fake, fake, stream=0)
+    assert e.value.status == B.EINVAL
+    big = good_layout(B, capacity=2049, window=1, n_q_heads=32, n_kv_heads=8, batch=16)
+    assert B.caote_workspace_bytes(big, 2048) > B.STATIC_SCRATCH_BYTES
+    with pytest.raises(B.CaoteError) as e:
+        B.caote_evict_static(fake, fake, fake, fake, big, 2048, 1, fake, fake, stream=0)
+    assert e.value.status == B.EWORKSPACE and "static" in str(e.value)
+    hdr = open(os.path.join(ROOT, "include", "caote.h")).read()
+    m = re.search(r"#define\s+CAOTE_STATIC_SCRATCH_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", hdr)
+    assert int(m.group(1)) << int(m.group(2)) == B.STATIC_SCRATCH_BYTES
