@@ -25,6 +25,9 @@
  *     window_in_cache is set (1 <= N_b otherwise); values of seq_lens outside
  *     [0, capacity] are clamped on the device, so no access leaves the buffers.
  *
+ *   - q_window, K and V must be 16-byte aligned (their strides too): rows are fetched
+ *     in 16-byte pieces.  Misaligned pointers are rejected with CAOTE_EINVAL.
+ *
  * Shapes (row-major, innermost dimension contiguous, strides in ELEMENTS)
  *   q_window  [batch][n_q_heads][window][head_dim]     dtype   (strides q_stride_*)
  *   K, V      [batch][n_kv_heads][capacity][head_dim]  dtype   (strides k_/v_stride_*)
@@ -59,7 +62,7 @@ typedef enum {
   CAOTE_BASE_NONE = 0,   /* h = a.  With window = 1 and one query head per KV head
                             this is TOVA's last-row score (Sec. 2).                 */
   CAOTE_BASE_H2O = 1,    /* h = base_score + a, written back to base_score: the
-                            accumulated attention of H2O (Sec. 3.2, App. C.1).      */
+                            accumulated attention of H2O (Sec. 3.2, App. D.1).      */
   CAOTE_BASE_SNAPKV = 2  /* h = 1-D max-pool (width pool_kernel, stride 1, window
                             clipped at the ends of the scored range) of a.          */
 } caote_base;
@@ -91,8 +94,12 @@ typedef struct caote_layout {
   int32_t window_in_cache;   /* 1: the last W rows of K/V are the window's own
                                 tokens and attention inside the window is causal
                                 (block-wise prefill, Sec. 2); 0: every key visible    */
-  int32_t n_protect_head;    /* first rows are never evicted                          */
-  int32_t n_protect_tail;    /* last rows are never evicted (SnapKV: the window)      */
+  int32_t n_protect_head;    /* first rows are not scored: their score is +INF        */
+  int32_t n_protect_tail;    /* last rows likewise (SnapKV: the window).  Protected
+                                rows count against the budget and outrank every scored
+                                row, so none of them is evicted while budget >= their
+                                number; a smaller budget keeps the protected rows of
+                                lowest index (the tie rule of caote_select)            */
   int32_t variant;           /* caote_variant                                         */
   const float* row_lse;      /* DEVICE [batch][n_q_heads][window] fp32, dense, or NULL.
                                 Softmax normalisers handed over by the caller's own

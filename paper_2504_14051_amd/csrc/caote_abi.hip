@@ -170,6 +170,14 @@ caote_status check_ws(const caote_layout* L, int32_t budget, void* ws, size_t ws
   return CAOTE_OK;
 }
 
+// The kernels fetch rows of q, K and V in 16-byte pieces (DMA into LDS, uint4 loads): with the
+// strides already multiples of 16 bytes, the base addresses have to be too.
+caote_status check_aligned16(const void* q, const void* K, const void* V) {
+  if ((((uintptr_t)q) | ((uintptr_t)K) | ((uintptr_t)V)) % 16 != 0)
+    return fail(CAOTE_EINVAL, "q_window, K and V must be 16-byte aligned");
+  return CAOTE_OK;
+}
+
 caote_status device_status(hipError_t e, const char* what) {
   if (e == hipSuccess) return CAOTE_OK;
   return fail(CAOTE_EDEVICE, "%s: %s", what, hipGetErrorString(e));
@@ -264,6 +272,7 @@ caote_status caote_score(const void* q_window, const void* K, const void* V, flo
   caote_status st = check_layout(layout, 0, false);
   if (st != CAOTE_OK) return st;
   if (!q_window || !K || !V || !scores) return fail(CAOTE_EINVAL, "q_window, K, V and scores must not be NULL");
+  if ((st = check_aligned16(q_window, K, V)) != CAOTE_OK) return st;
   if (layout->base == CAOTE_BASE_H2O && !base_score)
     return fail(CAOTE_EINVAL, "CAOTE_BASE_H2O needs base_score (the accumulator)");
   Params p;
@@ -294,6 +303,7 @@ caote_status caote_compact(void* K, void* V, float* base_score, const int32_t* k
   caote_status st = check_layout(layout, budget, true);
   if (st != CAOTE_OK) return st;
   if (!K || !V || !kept_idx) return fail(CAOTE_EINVAL, "K, V and kept_idx must not be NULL");
+  if ((st = check_aligned16(nullptr, K, V)) != CAOTE_OK) return st;
   if (mode != CAOTE_COMPACT_STABLE && mode != CAOTE_COMPACT_SWAP_LAST)
     return fail(CAOTE_EINVAL, "unknown compaction mode %d", mode);
   Params p;
@@ -309,6 +319,7 @@ caote_status caote_append(void* K, void* V, float* base_score, const void* k_new
   caote_status st = check_layout(layout, 0, false);
   if (st != CAOTE_OK) return st;
   if (!K || !V || !k_new || !v_new) return fail(CAOTE_EINVAL, "K, V, k_new and v_new must not be NULL");
+  if ((st = check_aligned16(nullptr, K, V)) != CAOTE_OK) return st;
   if (n_new < 0) return fail(CAOTE_EINVAL, "n_new must be >= 0");
   if (!layout->seq_lens && (n_at < 0 || (int64_t)n_at + n_new > layout->capacity))
     return fail(CAOTE_EINVAL, "rows [%d, %d) do not fit the capacity %d", n_at, n_at + n_new,
@@ -344,6 +355,7 @@ static caote_status check_evict_args(const void* q_window, const void* K, const 
   }
   if (!q_window || !K || !V || !scores || !kept_idx)
     return fail(CAOTE_EINVAL, "q_window, K, V, scores and kept_idx must not be NULL");
+  if ((st = check_aligned16(q_window, K, V)) != CAOTE_OK) return st;
   if (layout->base == CAOTE_BASE_H2O && !base_score)
     return fail(CAOTE_EINVAL, "CAOTE_BASE_H2O needs base_score (the accumulator)");
   if (mode != CAOTE_COMPACT_STABLE && mode != CAOTE_COMPACT_SWAP_LAST)

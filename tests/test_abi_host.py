@@ -180,6 +180,30 @@ def test_read_stream_arguments_are_checked_on_the_host(B):
     B.caote_read_stream(fake, 0, fake, stream=0)                 # nothing to read: no launch
 
 
+def test_misaligned_data_pointers_are_rejected(B):
+    """q, K and V are fetched in 16-byte pieces: a base address off that grid is refused on the
+    host by every entry point that reads them."""
+    L = good_layout(B)
+    fake, ws = 0x1000, 0x10000
+    need = B.caote_workspace_bytes(L, 64)
+    for q, K, V in ((fake + 8, fake, fake), (fake, fake + 2, fake), (fake, fake, fake + 4)):
+        with pytest.raises(B.CaoteError) as e:
+            B.caote_score(q, K, V, fake, L, fake, ws, stream=0, workspace_bytes=need)
+        assert e.value.status == B.EINVAL and "aligned" in str(e.value)
+        with pytest.raises(B.CaoteError) as e:
+            B.caote_evict(q, K, V, fake, L, 64, 0, fake, fake, ws, stream=0, workspace_bytes=need)
+        assert e.value.status == B.EINVAL and "aligned" in str(e.value)
+        with pytest.raises(B.CaoteError) as e:
+            B.caote_evict_static(q, K, V, fake, L, 64, 0, fake, fake, stream=0)
+        assert e.value.status == B.EINVAL and "aligned" in str(e.value)
+    with pytest.raises(B.CaoteError) as e:
+        B.caote_compact(fake + 8, fake, None, fake, L, 64, 0, ws, stream=0, workspace_bytes=need)
+    assert e.value.status == B.EINVAL and "aligned" in str(e.value)
+    with pytest.raises(B.CaoteError) as e:
+        B.caote_append(fake, fake + 8, None, fake, fake, L, 0, 4, stream=0)
+    assert e.value.status == B.EINVAL and "aligned" in str(e.value)
+
+
 def test_static_scratch_entry_point_checks_arguments_and_size_on_the_host(B):
     """caote_evict_static: the same argument checks as caote_evict, and a layout whose scratch
     does not fit the fixed array is refused before any device call is made."""
