@@ -384,7 +384,7 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
   // up to 128 scoring workgroups per head add to the same few dozen bins: beyond that the
   // serialised device atomics outlast the kernel, and a histogram kernel of its own is faster
   p.hist_in_vscore = (p.cap > 16384 && p.cap <= 32768 && p.hist_zeroed) ? 1 : 0;
-  p.select_swaps = p.cap <= 16384 ? 1 : 0;  // (the one-workgroup selections of launch_select)
+  p.select_swaps = p.cap <= caote::kOneWgCap ? 1 : 0;  // (the one-workgroup selections of launch_select)
   p.combine_in_select = (p.vside_cs && !joint) ? 1 : 0;   // (k_vside caches are short: one-workgroup selection)
   if (joint) p.hist_in_vscore = p.select_swaps = 0;
   if (layout->base == CAOTE_BASE_H2O && !p.vside_cs) p.h = base_score;

@@ -15,6 +15,7 @@ constexpr int kHistBins = 4096;   // selection histogram: top 12 bits of the sco
 constexpr int kHistShift = 20;
 constexpr int kSelSpan = 2048;    // tokens per workgroup in the selection kernels
 constexpr int kMaxSpans = 1024;   // spans per head the selection supports (2M tokens)
+constexpr int kOneWgCap = 16384;  // largest cache whose selection one workgroup per head does alone
 constexpr int kVSideSlots = 34;   // short caches: value rows a lane keeps in registers (k_vside)
 constexpr int kJointMaxCap = CAOTE_JOINT_MAX_CAPACITY;   // greedy joint eviction: weights of a head fit LDS
 

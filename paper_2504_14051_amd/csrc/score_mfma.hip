@@ -11,9 +11,11 @@
 // row/column l%32, k = 8*(l/32)..+7), so the same Q registers and the same K reads from
 // LDS serve both sweeps.
 //
-// A workgroup is 4 waves arranged WR (row waves) x WK (key waves); every wave keeps RBW
-// 32-row blocks of Q in registers for the whole sweep.  K tiles of 64 keys go through a
-// double-buffered, XOR-swizzled LDS stage: global -> registers one tile ahead -> LDS.
+// A workgroup is 4 or 8 waves arranged WR (row waves) x WK (key waves); every wave keeps RBW
+// 32-row blocks of Q in registers for the whole sweep.  K tiles of 64 keys arrive in a
+// three-slot, XOR-swizzled LDS ring by DMA (global_load_lds_dwordx4, two tiles ahead of the
+// math, waits counted by hand); in the fused second sweep the V rows of each tile follow
+// into a two-slot ring of their own, requested two iterations before they are added up.
 #include <type_traits>
 
 #include "common.hpp"
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   __shared__ float af[FUSE ? 4 * kTN : 1];
   __shared__ float hw[FUSE ? 4 * kTN : 1];
   __shared__ float bs[2][FUSE ? kTN : 1];
-  __shared__ __attribute__((aligned(16))) unsigned char Vs[FUSE ? kTN * kRowBytes : 16];
+  __shared__ __attribute__((aligned(16))) unsigned char Vs[2][FUSE ? kTN * kRowBytes : 16];
 
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.K) +
                             ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * 2;
@@ -198,7 +200,9 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
     }
     // One 64-key tile out of LDS buffer `buf`.  TAIL: some logits of the tile are masked
     // (keys past the end of the cache, or window keys a row must not see).
-    auto tile = [&](auto tail_tag, int buf, int abuf, int tile0) {
+    // `mid` runs once, right after the matrix instructions of the first key block have been
+    // issued: work that waits on LDS round trips of its own goes there, under their shadow.
+    auto tile = [&](auto tail_tag, int buf, int abuf, int tile0, auto&& mid) {
       constexpr bool TAIL = decltype(tail_tag)::value;
 #pragma unroll
       for (int kbi = 0; kbi < KBW; ++kbi) {
@@ -220,6 +224,7 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
             else           acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[rb][ks], kf[ks], cin, 0, 0, 0);
           }
         }
+        if (kbi == 0) mid();
         const int jb = tile0 + kb * 32;                       // first key of the block
         if (MODE == 0) {
 #pragma unroll
@@ -279,10 +284,10 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
         }
       }
     };
-    auto math = [&](int t, int buf, int abuf) {
+    auto math = [&](int t, int buf, int abuf, auto&& mid) {
       const int tile0 = c0 + t * kTN;
-      if (tile0 + kTN > min(P, N)) tile(std::true_type{}, buf, abuf, tile0);
-      else                         tile(std::false_type{}, buf, abuf, tile0);
+      if (tile0 + kTN > min(P, N)) tile(std::true_type{}, buf, abuf, tile0, mid);
+      else                         tile(std::false_type{}, buf, abuf, tile0, mid);
     };
     // ---- FUSE: the value sum rides along (Sec. 3.2: o = sum_j w_j v_j) ---------------------
     // Value step s covers the 64 keys c0 + 64 s - halo ... (shifted down by the pooling
@@ -321,8 +326,16 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
             if (p.base_mode == CAOTE_BASE_H2O) {
               hj += bs[t & 1][tid];
             } else if (p.base_mode == CAOTE_BASE_SNAPKV && scored) {
+              // eight neighbours per round of LDS reads (indices past the window's end repeat
+              // its last key, which changes no maximum): pool width 7 is one round trip
               const int t0 = max(lo, j - halo), t1 = min(hi - 1, j + halo);
-              for (int tt = t0; tt <= t1; ++tt) hj = fmaxf(hj, af[(tt - c0) & (4 * kTN - 1)]);
+              for (int tb = t0; tb <= t1; tb += 8) {
+                float x[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = af[(min(tb + u, t1) - c0) & (4 * kTN - 1)];
+                hj = fmaxf(fmaxf(fmaxf(hj, x[0]), fmaxf(x[1], x[2])),
+                           fmaxf(fmaxf(x[3], x[4]), fmaxf(fmaxf(x[5], x[6]), x[7])));
+              }
             }
             p.h[(int64_t)bh * p.cap + j] = hj;
           }
@@ -356,11 +369,22 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
       const int j = min(max(c0 + s * kTN - halo + lane, 0), N - 1);
       load_to_lds4(p.base + (int64_t)bh * p.cap + j, __builtin_amdgcn_readfirstlane(lds_addr(&bs[s & 1][0])));
     };
-    auto v_consume = [&](int s, const unsigned char* vs) {
+    // The V rows of a step and their weights come out of LDS in v_load; v_fma adds them up
+    // later, once the reads have surely returned.
+    uint4 vraw[LPT];
+    float vw[LPT];
+    auto v_load = [&](int s, const unsigned char* vs) {
 #pragma unroll
       for (int u = 0; u < LPT; ++u) {
-        const float w = hw[(s & 3) * kTN + wave * RW + u * 4 + (lane >> 4)];
-        const uint4 raw = *reinterpret_cast<const uint4*>(vs + ((wave * LPT + u) * kWave + lane) * 16);
+        vw[u] = hw[(s & 3) * kTN + wave * RW + u * 4 + (lane >> 4)];
+        vraw[u] = *reinterpret_cast<const uint4*>(vs + ((wave * LPT + u) * kWave + lane) * 16);
+      }
+    };
+    auto v_fma = [&]() {
+#pragma unroll
+      for (int u = 0; u < LPT; ++u) {
+        const float w = vw[u];
+        const uint4 raw = vraw[u];
         vacc[0] = fmaf(w, __uint_as_float(raw.x << 16), vacc[0]);
         vacc[1] = fmaf(w, __uint_as_float(raw.x & 0xffff0000u), vacc[1]);
         vacc[2] = fmaf(w, __uint_as_float(raw.y << 16), vacc[2]);
@@ -371,6 +395,7 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
         vacc[7] = fmaf(w, __uint_as_float(raw.w & 0xffff0000u), vacc[7]);
       }
     };
+    auto v_consume = [&](int s, const unsigned char* vs) { v_load(s, vs); v_fma(); };
     // Make the compiler finish its own global loads (Q fragments, normalisers) here: a wait
     // it placed inside the tile loop would also drain the LDS loads that must stay in flight.
 #pragma unroll
@@ -385,31 +410,40 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
     if (vlast && p.base_mode == CAOTE_BASE_H2O && wave == 0) base_issue(0);
     int buf = 0;
     for (int t = 0; t < ntiles; ++t) {
-      // this wave's share of tile t has landed once at most the LPT loads of tile t+1 are
-      // still in flight (loads complete in order; a store in between cannot hide a load);
-      // so have the V rows requested in the last iteration, which are older than those
-      if (t + 1 < ntiles) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
-      __syncthreads();                   // ... and so has everyone else's; tile t-1 is done with
-      if (t > 0) flush_a(t - 1, (t - 1) & 1);
-      const int spare = buf == 0 ? kNBuf - 1 : buf - 1;     // ring slot of tile t-1
-      if (vlast) {
-        if (t >= 2) v_consume(t - 2, Vs);
-        if (t >= 1) v_issue(t - 1, Vs);
-        if (p.base_mode == CAOTE_BASE_H2O && wave == 0 && t + 1 < ntiles) base_issue(t + 1);
-        // the last tile's V rows go where the K tile t+2 would have gone
-        if (t == ntiles - 1) v_issue(t, &Ks[spare][0]);
+      // this wave's share of tile t has landed once only the loads requested after it are still
+      // in flight (loads complete in order; a store in between cannot hide a load): the K tile
+      // t+1 and, in the fused sweep, the V rows of step t-1, both requested in iteration t-1
+      if (vlast && t >= 1) {
+        if (t + 1 < ntiles) wait_vmcnt<2 * LPT>(); else wait_vmcnt<LPT>();
+      } else {
+        if (t + 1 < ntiles) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
       }
+      __syncthreads();                   // ... and so has everyone else's; tile t-1 is done with
+      const int spare = buf == 0 ? kNBuf - 1 : buf - 1;     // ring slot of tile t-1
       if (t + kNBuf - 1 < ntiles) issue(t + kNBuf - 1, spare);
-      math(t, buf, t & 1);
+      // The first wave turns the column sums of tile t-1 into weights (for value step t-1,
+      // next iteration).  Step t-2 of the value sum: its rows and weights are read out of LDS
+      // now and added up after this tile's matrix instructions have been issued.  The V rows of
+      // step t then go into the slot that step t-2 has been read from: two iterations pass
+      // between the request and the use.
+      if (t > 0) flush_a(t - 1, (t - 1) & 1);
+      if (vlast && t >= 2) v_load(t - 2, Vs[t & 1]);
+      math(t, buf, t & 1, [&]() {
+        if (vlast) {
+          if (t >= 2) v_fma();
+          v_issue(t, Vs[t & 1]);
+          if (p.base_mode == CAOTE_BASE_H2O && wave == 0 && t + 1 < ntiles) base_issue(t + 1);
+        }
+      });
       buf = buf + 1 == kNBuf ? 0 : buf + 1;
     }
     if (vlast) wait_vmcnt<0>();
     __syncthreads();
     flush_a(ntiles - 1, (ntiles - 1) & 1);
     if (vlast) {
-      if (ntiles >= 2) v_consume(ntiles - 2, Vs);
+      if (ntiles >= 2) v_consume(ntiles - 2, Vs[ntiles & 1]);
       __syncthreads();                   // the weights of the last step are in LDS
-      v_consume(ntiles - 1, &Ks[(ntiles + 1) % kNBuf][0]);
+      v_consume(ntiles - 1, Vs[(ntiles - 1) & 1]);
       // partial sums of this chunk: over the four teams of a wave, then over the waves
 #pragma unroll
       for (int e = 0; e < 8; ++e) {

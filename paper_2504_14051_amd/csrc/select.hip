@@ -22,7 +22,8 @@ constexpr int kT = 256;                   // threads per workgroup
 constexpr int kW = kT / kWave;            // waves per workgroup
 constexpr int kPer = kSelSpan / kT;       // tokens per thread in a span (8)
 constexpr int kRows = kSelSpan / kW / kWave;   // 64-token rows per wave (8)
-constexpr int kSmallCand = 128;           // candidate lists up to this length are ranked in LDS
+constexpr int kSmallCand = 128;           // candidate lists up to this length are ranked against each other
+constexpr int kCandCap = 4096;            // candidate lists up to this length are searched in LDS
 static_assert(kPer * kT == kSelSpan && kRows * kW * kWave == kSelSpan, "span geometry");
 static_assert(kHistShift == 20, "the one-workgroup selection splits the open bits 10 + 10");
 
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
   __shared__ int pre[kMaxSpans + 1];
   __shared__ uint32_t s_prefix;
   __shared__ int s_krem, s_off, s_ties;
-  __shared__ __attribute__((aligned(16))) uint32_t cl[kSmallCand];   // the head's candidates, if few
+  __shared__ __attribute__((aligned(16))) uint32_t cl[kCandCap];     // the head's candidates, if they fit
 
   uint32_t key[kRows];
   bool valid[kRows];
@@ -235,14 +236,34 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
     return cand[lo * kSelSpan + (i - pre[lo])];
   };
 
+  // The candidates come into LDS once, eight loads per thread in flight at a time (each is a
+  // dependent search in `pre` plus a load: one by one they would cost a round trip apiece).
+  const bool in_lds = ncand <= kCandCap;
+  const int n_pad = ((ncand + 3) & ~3) - ncand;         // zero keys that fill the last uint4
+  if (in_lds) {
+    constexpr int kCB = 8;
+    for (int i0 = 0; i0 < ncand; i0 += kCB * kT) {
+      uint32_t c[kCB];
+#pragma unroll
+      for (int u = 0; u < kCB; ++u) {
+        const int i = i0 + u * kT + tid;
+        c[u] = i < ncand ? cand_at(i) : 0u;
+      }
+#pragma unroll
+      for (int u = 0; u < kCB; ++u) {
+        const int i = i0 + u * kT + tid;
+        if (i < ncand) cl[i] = c[u];
+      }
+    }
+    if (tid < n_pad) cl[ncand + tid] = 0u;
+  }
+  auto cand_of = [&](int i) -> uint32_t { return in_lds ? cl[i] : cand_at(i); };
+
   uint32_t theta;                         // key of the k-th largest score
   if (ncand <= kSmallCand) {
     // ---- few candidates: rank them against each other in LDS ------------------------------------
     // theta is the candidate with fewer than krem candidates above it and at least krem at or
     // above it; the same pass over the list gives the counts of the earlier spans.
-    for (int i = tid; i < ncand; i += kT) cl[i] = cand_at(i);
-    const int n_pad = ((ncand + 3) & ~3) - ncand;       // zero keys that fill the last uint4
-    if (tid < n_pad) cl[ncand + tid] = 0u;
     if (tid == 0) { s_prefix = prefix; s_krem = 0; }    // (no candidate: not reached, krem >= 1)
     __syncthreads();
     for (int i = tid; i < ncand; i += kT) {
@@ -274,6 +295,7 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
     __syncthreads();
   } else {
     // ---- finish the radix search on the low 20 bits, over every span's candidates -----------
+    __syncthreads();                        // the list is in LDS
     int shift = kHistShift;
     while (shift > 0) {
       const int bits = shift >= 8 ? 8 : shift;
@@ -282,7 +304,7 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
       hist[tid] = 0;
       __syncthreads();
       for (int i = tid; i < ncand; i += kT) {
-        const uint32_t ck = cand_at(i);
+        const uint32_t ck = cand_of(i);
         if ((ck & himask) == prefix) atomicAdd(&hist[(ck >> shift) & ((1u << bits) - 1u)], 1);
       }
       __syncthreads();
@@ -310,7 +332,7 @@ __global__ __launch_bounds__(kT) void k_select_emit(const Params p) {
     {
       int gt = 0, eq = 0;
       for (int i = tid; i < pre[me]; i += kT) {
-        const uint32_t ck = cand_at(i);
+        const uint32_t ck = cand_of(i);
         gt += ck > theta;
         eq += ck == theta;
       }
@@ -370,7 +392,7 @@ constexpr int kST = 1024;                 // threads
 constexpr int kSW = kST / kWave;          // waves
 constexpr int kSPer = 4;                  // tokens per thread
 constexpr int kSmallCap = kST * kSPer;    // 4096
-constexpr int kOneWgCap = 4 * kSmallCap;  // 16384: largest cache that one workgroup selects from
+static_assert(kOneWgCap == 4 * kSmallCap, "one workgroup holds at most four rows of 4096 tokens per thread");
 
 // Exclusive prefix sum over the 1024 threads, and the total.  wave_tot: kSW ints of LDS.
 __device__ __forceinline__ int block_excl_scan_1024(int v, int* wave_tot, int& total) {
