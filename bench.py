@@ -7,11 +7,14 @@ several independent layer buffers so that K and V come from HBM, not from the 25
 Infinity Cache.  Prints ONE JSON line:
 
   metric/value  cached tokens scored+evicted per second per layer (all heads)
-  roofline      the slowest kernel of the path: its own compulsory HBM bytes / its mean
-                duration (HIP events on the launch stream) against the 8 TB/s peak
+  roofline      the slowest kernel of the path: its own compulsory HBM bytes / its duration
+                against the 8 TB/s peak.  A kernel's duration is the replay time of the call
+                cut after that kernel minus that of the call cut before it (caote_evict_prefix,
+                same graph, same rotation of buffers): kernel time, not gaps between events
   path          the whole path's algorithmic bytes / step time against the same peak
-  cpu_baseline  the fp64 oracle on the host cores, same workload (a reported baseline,
-                not a target)
+  step_time_us  median / p10 / p90 of single steps (one graph replay each between two events)
+  cpu_baseline  the fp64 oracle on the host, same workload, on all cores it can use and on one
+                thread (a reported baseline, not a target)
 """
 from __future__ import annotations
 
@@ -81,7 +84,7 @@ def phase_bytes(wl, name, fused_value_sum=False):
     return table.get(name)
 
 
-# Kernel(s) behind each phase name that caote_evict_timed reports.
+# Kernel(s) behind each phase name that caote_evict_prefix reports.
 PHASE_KERNELS = {
     "key_rowstats": r"k_logits_\w+<.*, 0>$", "key_colsum": r"k_logits_\w+<.*, [12]>$",
     "merge_stats": r"k_merge_stats", "value_sum": r"k_vsum", "value_final": r"k_vfinal",
@@ -346,20 +349,67 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = wl.batch * wl.context / (dt / args.steps)
 
-    # Per-kernel durations: the same call with a HIP event between its kernels, on the
-    # stream the kernels run on, over the same rotation of buffers.
-    n_timed = max(10, min(args.steps, 100))
-    acc = {}
-    for i in range(n_timed):
-        q, K, V, base = layers[i % n_layers]
-        for name, ms in B.caote_evict_timed(q, K, V, base, L, wl.budget, mode, scores, kept, ws, stream):
-            acc.setdefault(name, []).append(ms)
-    phases = {k: sum(v) / len(v) for k, v in acc.items()}
+    # Per-kernel durations: the call cut after its k-th kernel, for every k, each as a graph of
+    # the same steps over the same rotation of buffers; kernel k costs T(k) - T(k-1).
+    q, K, V, base = layers[0]
+    names = B.caote_evict_prefix(q, K, V, base, L, wl.budget, mode, scores, kept, ws, -1, stream)
+    torch.cuda.synchronize()
+
+    def prefix_time(k):
+        def step_k(i):
+            q, K, V, base = layers[i % n_layers]
+            append(i)
+            B.caote_evict_prefix(q, K, V, base, L, wl.budget, mode, scores, kept, ws, k, stream)
+        if k == 0 and not blockwise:
+            return 0.0
+        timed_replay(step_k, n_again=4)
+        return min(replays.pop()) * 1e-3 * args.steps
+
+    phases = {}
+    if args.no_graph:
+        phases = {"evict_fused": ms_per_step}
+    else:
+        t_prev = prefix_time(0)
+        for k, name in enumerate(names, start=1):
+            t_k = prefix_time(k)
+            phases[name] = max(t_k - t_prev, 0.0) / args.steps * 1e3
+            t_prev = t_k
     dom = max(phases, key=phases.get)
     dom_bytes = phase_bytes(wl, dom, fused_value_sum="key_colsum" in phases and "value_sum" not in phases)
     dom_gbs = dom_bytes / (phases[dom] * 1e-3) / 1e9
     alg = algorithmic_bytes(wl)
     path_gbs = alg["total"] / (ms_per_step * 1e-3) / 1e9
+
+    # Single steps: one graph per layer buffer holding one step, replayed in rotation between two
+    # events each (the queue stays ahead of the GPU, so an interval is one step plus the gap to the
+    # next graph launch).
+    dist = None
+    if not args.no_graph:
+        n_dist = max(200, args.steps)
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        outer = stream
+        with torch.cuda.stream(side):
+            stream = side
+            singles = []
+            for l in range(n_layers):
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    step(l)
+                singles.append(g)
+            for l in range(n_layers):
+                singles[l].replay()
+            side.synchronize()
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_dist)]
+            for i, (e0, e1) in enumerate(evs):
+                e0.record(side)
+                singles[i % n_layers].replay()
+                e1.record(side)
+            side.synchronize()
+            us = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in evs)
+            dist = {"n": n_dist, "median": us[n_dist // 2], "p10": us[n_dist // 10], "p90": us[(9 * n_dist) // 10],
+                    "note": "single-step graph replays between two events each; ms_per_step is the K-step graph"}
+        stream = outer
 
     out = {
         "metric": "cached tokens scored+evicted/sec per layer (all heads); % of HBM peak",
@@ -380,7 +430,10 @@ def main():
         "path": {"algorithmic_bytes": alg["total"], "achieved": path_gbs, "peak": HBM_PEAK_GBS,
                  "unit": "GB/s", "frac": path_gbs / HBM_PEAK_GBS},
         "phases_ms": phases,
+        "phases_note": "kernel k = replay time of the call cut after k kernels minus cut after k-1 (caote_evict_prefix)",
     }
+    if dist is not None:
+        out["step_time_us"] = dist
     if dt_lse is not None:
         out["given_row_lse"] = {
             "ms_per_step": dt_lse / args.steps * 1e3,
@@ -418,19 +471,41 @@ def main():
         sys.path.insert(0, os.path.join(ROOT, "tests"))
         import helpers as H
         oracle.build()
-        threads = H.host_threads()
-        t0 = time.perf_counter()
-        oc, oh, _ = H.oracle_scores(oracle, host, threads=threads)
-        kept_o = oracle.select_batched(oc, None, wl.budget)
-        for hk in range(wl.n_kv_heads):
-            oracle.compact_one(host.K[0, hk].view(torch.uint8).numpy(), kept_o[0, hk])
-            oracle.compact_one(host.V[0, hk].view(torch.uint8).numpy(), kept_o[0, hk])
-        t_cpu = time.perf_counter() - t0
+        n_tasks = wl.batch * wl.n_kv_heads               # the oracle runs one (sequence, KV head) per thread
+        host_cores = os.cpu_count() or 1
+
+        def oracle_layer(threads):
+            t0 = time.perf_counter()
+            oc, oh, _ = H.oracle_scores(oracle, host, threads=threads)
+            kept_o = oracle.select_batched(oc, None, wl.budget)
+            for b in range(wl.batch):
+                for hk in range(wl.n_kv_heads):
+                    oracle.compact_one(host.K[b, hk].view(torch.uint8).numpy(), kept_o[b, hk])
+                    oracle.compact_one(host.V[b, hk].view(torch.uint8).numpy(), kept_o[b, hk])
+            return time.perf_counter() - t0
+
+        used = max(1, min(host_cores, n_tasks))
+        t_all = oracle_layer(used)
+        # one thread: the whole layer if the all-cores run says it fits in about 30 s, else one
+        # (sequence, KV head) of it, scaled by the number of heads (stated in `sample`)
+        whole = t_all * used <= 30.0
+        if whole:
+            t_one = oracle_layer(1)
+            one_sample = "the same layer, one thread"
+        else:
+            sub = synth.Cache(wl.with_(batch=1, n_q_heads=wl.group, n_kv_heads=1), host.q[:1, :wl.group],
+                              host.K[:1, :1], host.V[:1, :1], host.base[:1, :1], None)
+            t0 = time.perf_counter()
+            H.oracle_scores(oracle, sub, threads=1)
+            t_one = (time.perf_counter() - t0) * n_tasks
+            one_sample = f"one (sequence, KV head) of the layer on one thread, times {n_tasks} (extrapolated)"
         out["cpu_baseline"] = {
-            "value": wl.batch * wl.context / t_cpu, "unit": "tokens/s", "cores": threads,
-            "kind": "oracle", "seconds": t_cpu,
-            "sample": f"one whole layer of the same workload (sequence 0, all {wl.n_kv_heads} KV heads): "
-                      "score + select + compact"}
+            "value": wl.batch * wl.context / t_all, "unit": "tokens/s", "cores": used,
+            "host_cores": host_cores, "kind": "oracle", "seconds": t_all,
+            "sample": f"one whole layer of the same workload (all {n_tasks} (sequence, KV head) pairs, one "
+                      f"thread each): score + select + compact",
+            "single_thread": {"value": wl.batch * wl.context / t_one, "unit": "tokens/s", "cores": 1,
+                              "seconds": t_one, "sample": one_sample}}
     print(json.dumps(out))
 
 

@@ -221,18 +221,21 @@ caote_status caote_evict_joint(const void* q_window, void* K, void* V, float* ba
                                float* joint_error, void* workspace, size_t workspace_bytes,
                                void* hip_stream);
 
-/* Measurement aid (benchmarks, profiling): caote_evict with a HIP event recorded
- * on `hip_stream` between its kernels.  Unlike every other entry point it creates
- * and destroys HIP events and WAITS for the stream before returning.
- *   phase_ms  HOST out [CAOTE_MAX_PHASES]: milliseconds between consecutive events
- *   n_phases  HOST out: number of phases filled in
- * caote_phase_name(i) names phase i of the calling thread's last timed call.      */
+/* Measurement aid (benchmarks, profiling): enqueues only the first `n_kernels` kernels of
+ * the caote_evict call with these arguments (all of them if n_kernels is negative or larger
+ * than the call has; none if it is 0).  Like caote_evict it neither allocates nor
+ * synchronises, so a stream of truncated calls can be captured and replayed; the time of a
+ * call's k-th kernel is the time of the call cut after k kernels minus that of the call cut
+ * after k-1.  A truncated call leaves scores, kept_idx and the caches in whatever state the
+ * kernels that ran have produced.
+ *   n_launched  HOST out (may be NULL): kernels enqueued
+ * caote_phase_name(i) names kernel i of the calling thread's last such call.            */
 #define CAOTE_MAX_PHASES 16
-caote_status caote_evict_timed(const void* q_window, void* K, void* V, float* base_score,
-                               const caote_layout* layout, int32_t budget, int32_t mode,
-                               float* scores, int32_t* kept_idx, void* workspace,
-                               size_t workspace_bytes, void* hip_stream, float* phase_ms,
-                               int32_t* n_phases);
+caote_status caote_evict_prefix(const void* q_window, void* K, void* V, float* base_score,
+                                const caote_layout* layout, int32_t budget, int32_t mode,
+                                float* scores, int32_t* kept_idx, void* workspace,
+                                size_t workspace_bytes, void* hip_stream, int32_t n_kernels,
+                                int32_t* n_launched);
 const char* caote_phase_name(int32_t i);
 
 /* Measurement aid: reads `bytes` of device memory at `buf` once with plain 16-byte loads and

@@ -22,7 +22,7 @@ EXACT, FAST = 0, 1
 COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
 
 EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
-           "caote_append", "caote_evict", "caote_evict_static", "caote_evict_joint", "caote_evict_timed", "caote_read_stream", "caote_phase_name", "caote_last_error",
+           "caote_append", "caote_evict", "caote_evict_static", "caote_evict_joint", "caote_evict_prefix", "caote_read_stream", "caote_phase_name", "caote_last_error",
            "caote_version")
 MAX_PHASES = 16
 JOINT_MAX_CAPACITY = 8192
@@ -81,9 +81,9 @@ def lib() -> ctypes.CDLL:
         L.caote_evict_static.restype = ctypes.c_int
         L.caote_evict_joint.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.caote_evict_joint.restype = ctypes.c_int
-        L.caote_evict_timed.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp,
-                                        ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
-        L.caote_evict_timed.restype = ctypes.c_int
+        L.caote_evict_prefix.argtypes = [vp, vp, vp, vp, lp, i32, i32, vp, vp, vp, sz, vp, i32,
+                                         ctypes.POINTER(i32)]
+        L.caote_evict_prefix.restype = ctypes.c_int
         L.caote_read_stream.argtypes = [vp, sz, vp, vp]
         L.caote_read_stream.restype = ctypes.c_int
         L.caote_phase_name.argtypes = [i32]
@@ -208,18 +208,17 @@ def caote_evict_joint(q_window, K, V, base_score, layout: Layout, budget: int, m
                                    _stream(stream)))
 
 
-def caote_evict_timed(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores,
-                      kept_idx, workspace, stream=None, workspace_bytes=None):
-    """caote_evict with HIP events between its kernels; waits for the stream.
-    Returns [(phase name, milliseconds), ...]."""
+def caote_evict_prefix(q_window, K, V, base_score, layout: Layout, budget: int, mode, scores,
+                       kept_idx, workspace, n_kernels: int, stream=None, workspace_bytes=None):
+    """Measurement aid: only the first `n_kernels` kernels of the caote_evict call (all if
+    negative).  Returns the names of the kernels that were enqueued."""
     wb = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
-    ms = (ctypes.c_float * MAX_PHASES)()
     n = ctypes.c_int32(0)
-    _check(lib().caote_evict_timed(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
-                                   ctypes.byref(layout), budget, mode, _ptr(scores),
-                                   _ptr(kept_idx), _ptr(workspace), wb, _stream(stream), ms,
-                                   ctypes.byref(n)))
-    return [(lib().caote_phase_name(i).decode(), float(ms[i])) for i in range(n.value)]
+    _check(lib().caote_evict_prefix(_ptr(q_window), _ptr(K), _ptr(V), _ptr(base_score),
+                                    ctypes.byref(layout), budget, mode, _ptr(scores),
+                                    _ptr(kept_idx), _ptr(workspace), wb, _stream(stream), n_kernels,
+                                    ctypes.byref(n)))
+    return [lib().caote_phase_name(i).decode() for i in range(min(n.value, MAX_PHASES))]
 
 
 def caote_read_stream(buf, nbytes: int, sink, stream=None) -> None:

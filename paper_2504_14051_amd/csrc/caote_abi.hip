@@ -183,38 +183,30 @@ caote_status device_status(hipError_t e, const char* what) {
   return fail(CAOTE_EDEVICE, "%s: %s", what, hipGetErrorString(e));
 }
 
-caote_status do_score(Params& p, hipStream_t s, caote::PhaseHook* hook = nullptr) {
+// Measurement aid: counts and names the kernels of one call and stops the call after the
+// first `limit` of them.
+struct PrefixHook final : caote::PhaseHook {
+  const char* names[CAOTE_MAX_PHASES];
+  int n = 0, limit;
+  explicit PrefixHook(int lim) : limit(lim) {}
+  bool mark(const char* name) override {
+    if (n < CAOTE_MAX_PHASES) names[n] = name;
+    ++n;
+    return limit >= 0 && n >= limit;
+  }
+  bool full() const override { return limit >= 0 && n >= limit; }
+};
+
+caote_status do_score(Params& p, hipStream_t s, PrefixHook* hook = nullptr) {
   hipError_t e = p.use_mfma   ? caote::launch_score_mfma(p, s, hook)
                  : p.small_r  ? (p.dtype == CAOTE_BF16 && p.D == 128 ? caote::launch_score_few_mfma(p, s, hook)
                                                                     : caote::launch_score_small(p, s, hook))
                               : caote::launch_score_generic(p, s, hook);
   if (e != hipSuccess) return device_status(e, "score (key sweeps)");
+  if (hook && hook->full()) return CAOTE_OK;
   return device_status(p.vside_cs ? caote::launch_value_side(p, s, hook) : caote::launch_value_passes(p, s, hook),
                        "score (value sweeps)");
 }
-
-// Measurement aid: events recorded between the kernels of one call.
-struct PhaseClock final : caote::PhaseHook {
-  hipStream_t stream;
-  hipEvent_t ev[CAOTE_MAX_PHASES + 1];
-  const char* names[CAOTE_MAX_PHASES];
-  int n = 0, n_ev = 0;
-  bool ok = true;
-  explicit PhaseClock(hipStream_t s) : stream(s) {
-    for (auto& e : ev) {
-      if (hipEventCreate(&e) != hipSuccess) { ok = false; break; }
-      ++n_ev;
-    }
-    if (ok) ok = hipEventRecord(ev[0], stream) == hipSuccess;
-  }
-  ~PhaseClock() { for (int i = 0; i < n_ev; ++i) (void)hipEventDestroy(ev[i]); }
-  void mark(const char* name) override {
-    if (!ok || n >= CAOTE_MAX_PHASES) return;
-    names[n] = name;
-    ok = hipEventRecord(ev[n + 1], stream) == hipSuccess;
-    ++n;
-  }
-};
 
 thread_local const char* g_phase_names[CAOTE_MAX_PHASES] = {};
 
@@ -367,9 +359,10 @@ static caote_status check_evict_args(const void* q_window, const void* K, const 
 static caote_status evict_impl(const void* q_window, void* K, void* V, float* base_score,
                                const caote_layout* layout, int32_t budget, int32_t mode,
                                float* scores, int32_t* kept_idx, void* workspace,
-                               size_t workspace_bytes, hipStream_t s, caote::PhaseHook* hook,
+                               size_t workspace_bytes, hipStream_t s, PrefixHook* prefix,
                                bool joint = false, int32_t* evicted = nullptr,
                                float* joint_error = nullptr) {
+  PrefixHook* hook = prefix;
   caote_status st = check_evict_args(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx,
                                      joint, evicted, joint_error);
   if (st != CAOTE_OK) return st;
@@ -389,14 +382,14 @@ static caote_status evict_impl(const void* q_window, void* K, void* V, float* ba
   if (joint) p.hist_in_vscore = p.select_swaps = 0;
   if (layout->base == CAOTE_BASE_H2O && !p.vside_cs) p.h = base_score;
   st = do_score(p, s, hook);
-  if (st != CAOTE_OK) return st;
+  if (st != CAOTE_OK || (prefix && prefix->full())) return st;
   if (joint) {
     const int max_evict = p.cap > budget ? p.cap - budget : 0;
     st = device_status(caote::launch_select_joint(p, evicted, joint_error, max_evict, s, hook), "select (joint)");
   } else {
     st = device_status(caote::launch_select(p, s, hook), "select");
   }
-  if (st != CAOTE_OK) return st;
+  if (st != CAOTE_OK || (prefix && prefix->full())) return st;
   return device_status(caote::launch_compact(p, s, hook), "compact");
 }
 
@@ -436,28 +429,21 @@ caote_status caote_evict_joint(const void* q_window, void* K, void* V, float* ba
                     workspace_bytes, (hipStream_t)hip_stream, nullptr, true, evicted, joint_error);
 }
 
-caote_status caote_evict_timed(const void* q_window, void* K, void* V, float* base_score,
-                               const caote_layout* layout, int32_t budget, int32_t mode,
-                               float* scores, int32_t* kept_idx, void* workspace,
-                               size_t workspace_bytes, void* hip_stream, float* phase_ms,
-                               int32_t* n_phases) {
-  if (!phase_ms || !n_phases) return fail(CAOTE_EINVAL, "phase_ms and n_phases must not be NULL");
-  hipStream_t s = (hipStream_t)hip_stream;
-  PhaseClock clock(s);
-  if (!clock.ok) return fail(CAOTE_EDEVICE, "could not create or record HIP events");
-  caote_status st = evict_impl(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx,
-                               workspace, workspace_bytes, s, &clock);
-  if (st != CAOTE_OK) return st;
-  if (!clock.ok) return fail(CAOTE_EDEVICE, "hipEventRecord failed");
-  hipError_t e = hipEventSynchronize(clock.ev[clock.n]);
-  if (e != hipSuccess) return device_status(e, "hipEventSynchronize");
-  for (int i = 0; i < clock.n; ++i) {
-    e = hipEventElapsedTime(&phase_ms[i], clock.ev[i], clock.ev[i + 1]);
-    if (e != hipSuccess) return device_status(e, "hipEventElapsedTime");
-    g_phase_names[i] = clock.names[i];
+caote_status caote_evict_prefix(const void* q_window, void* K, void* V, float* base_score,
+                                const caote_layout* layout, int32_t budget, int32_t mode,
+                                float* scores, int32_t* kept_idx, void* workspace,
+                                size_t workspace_bytes, void* hip_stream, int32_t n_kernels,
+                                int32_t* n_launched) {
+  PrefixHook hook(n_kernels);
+  if (n_kernels == 0) {
+    if (n_launched) *n_launched = 0;
+    return CAOTE_OK;
   }
-  for (int i = clock.n; i < CAOTE_MAX_PHASES; ++i) g_phase_names[i] = nullptr;
-  *n_phases = clock.n;
+  caote_status st = evict_impl(q_window, K, V, base_score, layout, budget, mode, scores, kept_idx,
+                               workspace, workspace_bytes, (hipStream_t)hip_stream, &hook);
+  if (st != CAOTE_OK) return st;
+  for (int i = 0; i < CAOTE_MAX_PHASES; ++i) g_phase_names[i] = i < hook.n ? hook.names[i] : nullptr;
+  if (n_launched) *n_launched = hook.n;
   return CAOTE_OK;
 }
 

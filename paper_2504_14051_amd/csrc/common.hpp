@@ -193,13 +193,16 @@ __device__ __forceinline__ uint32_t float_key(float f) {
 }
 
 // ---- launchers (one per source file) --------------------------------------------
-// A launcher calls hook->mark(name) after each kernel it enqueues (measurement aid).
+// A launcher calls mark(hook, name) after each kernel it enqueues (measurement aid); a true
+// return means: enqueue nothing more, return.
 struct PhaseHook {
-  virtual void mark(const char* name) = 0;
+  virtual bool mark(const char* name) = 0;
+  virtual bool full() const = 0;      // a launcher that another one called has been told to stop
  protected:
   ~PhaseHook() = default;
 };
-inline void mark(PhaseHook* h, const char* name) { if (h) h->mark(name); }
+inline bool mark(PhaseHook* h, const char* name) { return h && h->mark(name); }
+inline bool full(const PhaseHook* h) { return h && h->full(); }
 
 hipError_t launch_score_generic(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_score_mfma(const Params& p, hipStream_t s, PhaseHook* hook);

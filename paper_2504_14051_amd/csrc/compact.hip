@@ -156,15 +156,15 @@ hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook) {
   if (p.mode == CAOTE_COMPACT_SWAP_LAST) {
     if (!p.select_swaps) {               // else the selection kernel has moved the row already
       hipLaunchKernelGGL(k_swap_last, dim3(p.B * p.Hkv), dim3(kThreads), 0, s, p, row_bytes);
-      mark(hook, "compact_swap");
+      if (mark(hook, "compact_swap")) return hipGetLastError();
     }
     // with equal lengths and exactly one token over budget every sequence is an evict-one
     if (p.seq_lens == nullptr && p.cap - p.budget == 1) return hipGetLastError();
   }
   hipLaunchKernelGGL(k_move_rows<0>, grid, dim3(kThreads), 0, s, p, row_bytes);
-  mark(hook, "compact_gather");
+  if (mark(hook, "compact_gather")) return hipGetLastError();
   hipLaunchKernelGGL(k_move_rows<1>, grid, dim3(kThreads), 0, s, p, row_bytes);
-  mark(hook, "compact_scatter");
+  if (mark(hook, "compact_scatter")) return hipGetLastError();
   return hipGetLastError();
 }
 

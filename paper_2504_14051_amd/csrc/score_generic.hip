@@ -131,13 +131,13 @@ hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_split, p.B * p.Hkv);
   if (!p.lse_in) {                       // else the caller's attention pass has done sweep 1
     hipLaunchKernelGGL((k_logits_generic<T, D, 0>), grid, dim3(kThreads), 0, s, p);
-    mark(hook, "key_rowstats");
+    if (mark(hook, "key_rowstats")) return hipGetLastError();
     hipLaunchKernelGGL(k_merge_stats, dim3((p.R + 63) / 64, p.B * p.Hkv), dim3(64), 0, s, p);
-    mark(hook, "merge_stats");
+    if (mark(hook, "merge_stats")) return hipGetLastError();
   }
   hipLaunchKernelGGL((k_logits_generic<T, D, 1>), grid, dim3(kThreads),
                      (size_t)p.split_len * sizeof(float), s, p);
-  mark(hook, "key_colsum");
+  if (mark(hook, "key_colsum")) return hipGetLastError();
   return hipGetLastError();
 }
 

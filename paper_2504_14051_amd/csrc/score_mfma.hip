@@ -668,7 +668,7 @@ __global__ __launch_bounds__(kFewWaves * kWave) void k_rowstats_few_mfma(const P
 // multiple of 32.
 hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook) {
   hipLaunchKernelGGL(k_rowstats_few_mfma, dim3(p.n_split, p.B * p.Hkv), dim3(kFewWaves * kWave), 0, s, p);
-  mark(hook, "key_rowstats");
+  if (mark(hook, "key_rowstats")) return hipGetLastError();
   // the caller's normalisers: nothing to merge; short caches: the value kernel merges
   if (p.lse_in || p.merge_in_vside) return hipGetLastError();
   return launch_merge_stats(p, s, hook);
@@ -677,7 +677,7 @@ hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook
 
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook) {
   hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kMergeThreads), 0, s, p);
-  mark(hook, "merge_stats");
+  if (mark(hook, "merge_stats")) return hipGetLastError();
   return hipGetLastError();
 }
 
@@ -689,13 +689,13 @@ hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
   if (!p.lse_in) {                       // else the caller's attention pass has done sweep 1
     const dim3 grid0(p.n_split0, p.B * p.Hkv, p.n_rg0);
     hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid0, dim3(NWV * kWave), 0, s, p);
-    mark(hook, "key_rowstats");
+    if (mark(hook, "key_rowstats")) return hipGetLastError();
     const hipError_t e = launch_merge_stats(p, s, hook);
-    if (e != hipSuccess) return e;
+    if (e != hipSuccess || full(hook)) return e;
   }
   if (p.fuse_v) hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 2>), grid, dim3(NWV * kWave), 0, s, p);
   else          hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 1>), grid, dim3(NWV * kWave), 0, s, p);
-  mark(hook, "key_colsum");
+  if (mark(hook, "key_colsum")) return hipGetLastError();
   return hipGetLastError();
 }
 

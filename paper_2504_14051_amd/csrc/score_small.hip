@@ -128,7 +128,7 @@ hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
   const dim3 grid(p.n_split, p.B * p.Hkv);
   if (p.s_rows == 4) hipLaunchKernelGGL((k_rowstats_small<T, D, 4>), grid, dim3(kThreads), 0, s, p);
   else               hipLaunchKernelGGL((k_rowstats_small<T, D, 8>), grid, dim3(kThreads), 0, s, p);
-  mark(hook, "key_rowstats");
+  if (mark(hook, "key_rowstats")) return hipGetLastError();
   if (p.lse_in) return hipGetLastError();   // the caller's normalisers: nothing to merge
   return launch_merge_stats(p, s, hook);
 }

@@ -355,12 +355,12 @@ hipError_t launch_t(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int bh = p.B * p.Hkv;
   if (!p.fuse_v) {
     hipLaunchKernelGGL((k_vsum<T, D>), dim3(p.n_vsum, bh), dim3(kThreads), 0, s, p);
-    mark(hook, "value_sum");
+    if (mark(hook, "value_sum")) return hipGetLastError();
   }
   hipLaunchKernelGGL(k_vfinal, dim3(bh), dim3(kFinalThreads), 0, s, p);
-  mark(hook, "value_final");
+  if (mark(hook, "value_final")) return hipGetLastError();
   hipLaunchKernelGGL((k_vscore<T, D>), dim3(p.n_vchunk, bh), dim3(kThreads), 0, s, p);
-  mark(hook, "value_score");
+  if (mark(hook, "value_score")) return hipGetLastError();
   return hipGetLastError();
 }
 

@@ -266,17 +266,18 @@ __global__ __launch_bounds__(256) void k_vcombine(const Params p) {
 }
 
 template <int CS>
-void launch_cs(const Params& p, hipStream_t s, PhaseHook* hook) {
+hipError_t launch_cs(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int bh = p.B * p.Hkv;
   const dim3 grid(CS, bh);
   if (!p.small_r)         hipLaunchKernelGGL((k_vside<CS, 1>), grid, dim3(kVT), 0, s, p);
   else if (p.s_rows == 4) hipLaunchKernelGGL((k_vside<CS, 4>), grid, dim3(kVT), 0, s, p);
   else                    hipLaunchKernelGGL((k_vside<CS, 8>), grid, dim3(kVT), 0, s, p);
-  mark(hook, "value_side");
+  if (mark(hook, "value_side")) return hipGetLastError();
   if (!p.combine_in_select) {
     hipLaunchKernelGGL(k_vcombine, dim3((p.cap + 255) / 256, bh), dim3(256), 0, s, p);
-    mark(hook, "value_combine");
+    if (mark(hook, "value_combine")) return hipGetLastError();
   }
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -292,8 +293,7 @@ int vside_column_split(int cap) {
 
 hipError_t launch_value_side(const Params& p, hipStream_t s, PhaseHook* hook) {
   if (p.vside_cs != 2) return hipErrorInvalidValue;
-  launch_cs<2>(p, s, hook);
-  return hipGetLastError();
+  return launch_cs<2>(p, s, hook);
 }
 
 }  // namespace caote

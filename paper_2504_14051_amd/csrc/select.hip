@@ -768,19 +768,19 @@ hipError_t launch_select(const Params& p, hipStream_t s, PhaseHook* hook) {
     if (p.cap <= kSmallCap)          hipLaunchKernelGGL(k_select_small, dim3(bh), dim3(kST), 0, s, p, row_bytes);
     else if (p.cap <= 2 * kSmallCap) hipLaunchKernelGGL(k_select_one<2>, dim3(bh), dim3(kST), 0, s, p, row_bytes);
     else                             hipLaunchKernelGGL(k_select_one<4>, dim3(bh), dim3(kST), 0, s, p, row_bytes);
-    mark(hook, "select");
+    if (mark(hook, "select")) return hipGetLastError();
     return hipGetLastError();
   }
   if (!p.hist_zeroed) hipLaunchKernelGGL(k_select_zero, dim3(bh), dim3(kT), 0, s, p);
   if (!p.hist_in_vscore) {               // else the scoring kernel has built the histogram
     hipLaunchKernelGGL(k_select_hist, dim3((p.cap + 4095) / 4096, bh), dim3(1024), 0, s, p);
-    mark(hook, "select_hist");
+    if (mark(hook, "select_hist")) return hipGetLastError();
   }
   hipLaunchKernelGGL(k_select_span, dim3(p.n_span, bh), dim3(kT), 0, s, p);
-  mark(hook, "select_span");
+  if (mark(hook, "select_span")) return hipGetLastError();
   const int n_out = (max(p.cap, p.budget) + kSelSpan - 1) / kSelSpan;   // also pads past the cache
   hipLaunchKernelGGL(k_select_emit, dim3(n_out, bh), dim3(kT), 0, s, p);
-  mark(hook, "select_emit");
+  if (mark(hook, "select_emit")) return hipGetLastError();
   return hipGetLastError();
 }
 

@@ -325,9 +325,9 @@ hipError_t launch_t(const Params& p, int32_t* order, float* err, int max_evict, 
   const dim3 grid(p.j_c, p.B * p.Hkv);
   for (int t = 0; t < max_evict; ++t)
     hipLaunchKernelGGL((k_joint_step<T, D>), grid, dim3(kJT), 0, s, p, order, err, max_evict, t);
-  if (max_evict > 0) mark(hook, "select_joint_steps");
+  if (max_evict > 0 && mark(hook, "select_joint_steps")) return hipGetLastError();
   hipLaunchKernelGGL(k_joint_emit, dim3(p.B * p.Hkv), dim3(kET), 0, s, p, order, err, max_evict);
-  mark(hook, "select_joint_emit");
+  if (mark(hook, "select_joint_emit")) return hipGetLastError();
   return hipGetLastError();
 }
 

@@ -781,6 +781,35 @@ def test_hip_graph_replays_of_joint_eviction_match_eager(B):
         assert torch.equal(dev.base[:, :, :n], eb[:, :, :n])
 
 
+def test_truncated_calls_are_prefixes_of_the_fused_call(B):
+    """The measurement aid behind the benchmark's per-kernel times: cut after k kernels it enqueues
+    exactly the first k of the fused call's kernels, and uncut it is the fused call, bit for bit."""
+    for wl in (synth.llama3_8b_4k(), synth.decode_step(batch=2),
+               synth.llama3_8b_32k().with_(context=20000, budget=1500)):
+        cache = synth.make_cache(wl, base_init="random")
+        mode = 1 if wl.budget == wl.context - 1 else 0
+        ref = run_path(B, cache, wl.budget, mode, fused=True)
+        dev = H.to_device(cache)
+        L = B.layout_for(wl, dev)
+        ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
+        scores = torch.full(dev.K.shape[:3], float("nan"), device="cuda")
+        kept = torch.full((*dev.K.shape[:2], wl.budget), -7, dtype=torch.int32, device="cuda")
+        base = dev.base if wl.base == synth.BASE_H2O else None
+        names = B.caote_evict_prefix(dev.q, dev.K, dev.V, base, L, wl.budget, mode, scores, kept, ws, -1)
+        torch.cuda.synchronize()
+        assert 3 <= len(names) <= B.MAX_PHASES and all(names)
+        assert np.array_equal(scores.cpu().numpy(), ref["scores"], equal_nan=True)
+        assert np.array_equal(kept.cpu().numpy(), ref["kept"])
+        n = wl.budget
+        assert torch.equal(dev.K.cpu()[:, :, :n].view(torch.int16), ref["K_after"][:, :, :n].view(torch.int16))
+        dev2 = H.to_device(cache)
+        base2 = dev2.base if wl.base == synth.BASE_H2O else None
+        for k in range(len(names) + 2):
+            got = B.caote_evict_prefix(dev2.q, dev2.K, dev2.V, base2, L, wl.budget, mode, scores, kept, ws, k)
+            assert got == names[:k]
+        torch.cuda.synchronize()
+
+
 def test_read_stream_probe_runs_and_writes_nothing(B):
     """The measurement aid only reads: ragged sizes, the sink keeps its value."""
     buf = torch.arange(0, (1 << 20) + 48, dtype=torch.uint8, device="cuda")
