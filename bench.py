@@ -116,7 +116,11 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama3-8b-32k")
-    ap.add_argument("--layers", type=int, default=16, help="independent layer buffers to rotate over")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="independent layer buffers to rotate over (default 16; 32 for the decode stream: its model's depth)")
+    ap.add_argument("--ragged-prefill", action="store_true",
+                    help="decode workload: also time the ragged batch-16 prefill eviction (8k-32k tokens to 2048) "
+                         "that sets the stream up (generates 2 GiB of cache on the host first)")
     ap.add_argument("--batch", type=int, default=0, help="sequences per call (default: the workload's own)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
@@ -142,7 +146,8 @@ def main():
     if args.batch > 0:
         wl = wl.with_(batch=args.batch)
     host = synth.make_cache(wl)
-    n_layers = max(1, args.layers)
+    decode_stream = wl.name == "llama3-8b-decode"
+    n_layers = args.layers if args.layers > 0 else (32 if decode_stream else 16)
     mode = B.COMPACT_SWAP_LAST if swap_last(wl) else B.COMPACT_STABLE
 
     # Layer 0 is the generator's output; the others are the same tensors with the KV heads
@@ -466,6 +471,57 @@ def main():
             "note": "caote_evict_joint: the same step with the greedy selection under the joint "
                     "error: one kernel per evicted token, each step needs the one before"}
 
+    # The decode stream as the workload states it: one generation step is one evict-one call per
+    # layer, 32 layers with caches of their own, each layer's call after the one before (the
+    # model's own order).  Two more figures: the 32 calls of a step as ONE call over 32 x 16
+    # sequences (no dependency between layers: an upper bound), and, on request, the ragged
+    # prefill eviction that brings the 16 prompts down to the budget.
+    if decode_stream and not args.no_graph:
+        step_ms = ms_per_step * n_layers
+        out["decode_stream"] = {
+            "layers": n_layers, "sequences": wl.batch, "ms_per_generation_step": step_ms,
+            "tokens_per_s": wl.batch / (step_ms * 1e-3),
+            "cached_tokens_per_s": wl.batch * wl.context * n_layers / (step_ms * 1e-3),
+            "note": f"{n_layers} layers with independent caches, one call per layer in the model's order, "
+                    f"inside one HIP graph; a generation step appends one token to each of {wl.batch} sequences"}
+        Kb = torch.cat([K for (_, K, _, _) in layers], dim=0)
+        Vb = torch.cat([V for (_, _, V, _) in layers], dim=0)
+        qb = torch.cat([q for (q, _, _, _) in layers], dim=0)
+        bb = torch.cat([b for (_, _, _, b) in layers], dim=0)
+        Lb = B.make_layout(qb, Kb, Vb, base=wl.base, softmax_scale=wl.softmax_scale,
+                           window_in_cache=wl.window_in_cache, pool_kernel=wl.pool_kernel)
+        wsb = torch.empty(B.caote_workspace_bytes(Lb, wl.budget), dtype=torch.uint8, device="cuda")
+        sb = torch.empty(Kb.shape[:3], device="cuda")
+        kb = torch.empty((*Kb.shape[:2], wl.budget), dtype=torch.int32, device="cuda")
+        saved_steps = args.steps
+        args.steps = max(4, min(args.steps // n_layers, 20))
+        dt_b = timed_replay(lambda i: B.caote_evict(qb, Kb, Vb, bb, Lb, wl.budget, mode, sb, kb, wsb, stream))
+        out["decode_stream"]["all_layers_one_call"] = {
+            "ms_per_generation_step": dt_b / args.steps * 1e3, "steps": args.steps,
+            "note": f"the same step as one call over {Kb.shape[0]} sequences (all layers batched)"}
+        args.steps = saved_steps
+        del Kb, Vb, qb, bb, wsb, sb, kb
+    if decode_stream and args.ragged_prefill:
+        pw = synth.llama3_8b_32k().with_(batch=wl.batch, name="llama3-8b-prefill-ragged16")
+        lens = synth.prefill_lengths(pw.seed, pw.batch)
+        pc = synth.make_cache(pw, seq_lens=lens)
+        pq, pK, pV, pl = pc.q.cuda(), pc.K.cuda(), pc.V.cuda(), pc.seq_lens.cuda()
+        pL = B.make_layout(pq, pK, pV, base=pw.base, softmax_scale=pw.softmax_scale, pool_kernel=pw.pool_kernel,
+                           n_protect_tail=pw.n_protect_tail, seq_lens=pl)
+        pws = torch.empty(B.caote_workspace_bytes(pL, pw.budget), dtype=torch.uint8, device="cuda")
+        ps = torch.empty(pK.shape[:3], device="cuda")
+        pk = torch.empty((*pK.shape[:2], pw.budget), dtype=torch.int32, device="cuda")
+        saved_steps, saved_warm = args.steps, args.warmup
+        args.steps, args.warmup = 10, 2
+        dt_p = timed_replay(lambda i: B.caote_evict(pq, pK, pV, None, pL, pw.budget, B.COMPACT_STABLE, ps, pk, pws, stream))
+        out["ragged_prefill_eviction"] = {
+            "tokens": int(lens.sum()), "sequences": pw.batch, "ms_per_call": dt_p / args.steps * 1e3,
+            "value": float(lens.sum()) / (dt_p / args.steps), "unit": "tokens/s",
+            "note": "16 prompts of 8k-32k tokens cut to 2048 per KV head in one call with seq_lens (SnapKV base, "
+                    "window 64, pool 7); the caches are not restored between the timed calls"}
+        args.steps, args.warmup = saved_steps, saved_warm
+        del pq, pK, pV, pws, ps, pk, pc
+
     if not args.skip_cpu_baseline:
         import oracle
         sys.path.insert(0, os.path.join(ROOT, "tests"))
@@ -506,6 +562,10 @@ def main():
                       f"thread each): score + select + compact",
             "single_thread": {"value": wl.batch * wl.context / t_one, "unit": "tokens/s", "cores": 1,
                               "seconds": t_one, "sample": one_sample}}
+        if decode_stream:
+            out["cpu_baseline"]["generation_step_seconds_extrapolated"] = t_all * n_layers
+            out["cpu_baseline"]["sample"] += (f"; a generation step is {n_layers} such layers "
+                                              f"(extrapolated: {n_layers} x the measured layer)")
     print(json.dumps(out))
 
 
