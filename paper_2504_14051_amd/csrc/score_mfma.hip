@@ -72,7 +72,12 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   const int N = seq_len(p, b);
   // the first sweep may have its own split, with the row groups spread over the grid
   const int split_len = MODE == 0 ? p.split_len0 : p.split_len;
-  const int c0 = blockIdx.x * split_len;
+  // Which split of the head this workgroup takes rotates with the head: workgroups go to the
+  // eight compute dies round-robin by their linear index, and with ragged lengths the splits
+  // near the start of a sequence are full while those near its end are short or empty, so a
+  // fixed blockIdx.x -> split mapping would hand some dies twice the work of others.
+  const int split = (int)((blockIdx.x + (unsigned)bh) % gridDim.x);
+  const int c0 = split * split_len;
   // with the caller's normalisers this is the first kernel of the call: it clears the
   // selection's counters (otherwise the merge of the row statistics does)
   if (COLSUM && p.lse_in && blockIdx.x == 0) reset_counters(p, bh);
@@ -463,9 +468,9 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
         float sum = 0.f;
 #pragma unroll
         for (int w = 0; w < NWV; ++w) sum += red[w][tid];
-        p.opart[((int64_t)bh * p.n_vpart + blockIdx.x) * kD + tid] = sum;
+        p.opart[((int64_t)bh * p.n_vpart + split) * kD + tid] = sum;
       } else if (tid == kD) {
-        p.zpart[(int64_t)bh * p.n_vpart + blockIdx.x] = red[0][kD];
+        p.zpart[(int64_t)bh * p.n_vpart + split] = red[0][kD];
       }
     }
     // ---- end of sweep 1: merge the two half-waves, then the key waves ------------------
@@ -492,7 +497,7 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
 #pragma unroll
         for (int w = 0; w < WK; ++w)
           if (st_lds[w][rl][0] > -INFINITY) L += st_lds[w][rl][1] * exp2f(st_lds[w][rl][0] - M);
-        float* st = p.stats + (((int64_t)bh * p.n_split0 + blockIdx.x) * p.Rp + rg0 + rl) * 2;
+        float* st = p.stats + (((int64_t)bh * p.n_split0 + split) * p.Rp + rg0 + rl) * 2;
         st[0] = M; st[1] = L;
       }
     }
