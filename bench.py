@@ -127,6 +127,7 @@ def main():
     ap.add_argument("--calls-in-flight", type=int, default=4,
                     help="second figure: the same steps with this many calls (different layers) in flight "
                          "on streams of their own; 1 leaves it out")
+    ap.add_argument("--no-issue-probe", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (each (sequence, layer, KV head) is "
@@ -147,6 +148,7 @@ def main():
         wl = wl.with_(batch=args.batch)
     host = synth.make_cache(wl)
     decode_stream = wl.name == "llama3-8b-decode"
+    use_probe = wl.dtype == "bf16" and wl.head_dim == 128 and not args.no_issue_probe
     n_layers = args.layers if args.layers > 0 else (32 if decode_stream else 16)
     mode = B.COMPACT_SWAP_LAST if swap_last(wl) else B.COMPACT_STABLE
 
@@ -505,6 +507,25 @@ def main():
             "value": wl.batch * wl.context / (dt_two / args.steps), "unit": "tokens/s",
             "note": "the same K steps, step i (layer i mod layers) on stream i mod n: independent "
                     "calls overlap, total time / K"}
+    # What bounds a key sweep's arithmetic on this device: the per-tile instruction mix on
+    # registers only, matrix and vector work alone and together (caote_issue_probe).
+    if use_probe:
+        pb = torch.empty(B.ISSUE_PROBE_OUT_BYTES, dtype=torch.uint8, device="cuda")
+        iters = 2048
+        ns = {}
+        for v, name in enumerate(B.ISSUE_PROBE_VARIANTS):
+            B.caote_issue_probe(v, 64, pb, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            B.caote_issue_probe(v, iters, pb, stream)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ns[name] = e0.elapsed_time(e1) * 1e6 / iters
+        out["issue_probe"] = {
+            "ns_per_tile_two_waves_per_simd": ns,
+            "note": "256 workgroups of 8 waves, one per compute unit: time of one tile's worth of instructions per "
+                    "SIMD (two waves); mfma_then_vector lies between max(mfma_16, vector_block) (the two pipes overlap "
+                    "fully) and their sum (not at all): the arithmetic floor of a key sweep's tile"}
     if fast is not None:
         out["fastcaote"] = fast
     if dt_joint is not None:

@@ -244,6 +244,17 @@ const char* caote_phase_name(int32_t i);
  * sink: DEVICE, 4 bytes, in practice never written (it keeps the loads alive).           */
 caote_status caote_read_stream(const void* buf, size_t bytes, void* sink, void* hip_stream);
 
+/* Measurement aid: `iters` iterations of the instruction mix that one wave of the key sweeps
+ * issues per 64-key tile, on registers only, 256 workgroups of eight waves (as the sweeps
+ * run).  variant 0: the 16 matrix instructions alone; 1: the vector work alone (32 logits per
+ * lane: scale, exp2, maximum, sum); 2: both, the vector work on the matrix results; 3: 16 x
+ * (one matrix instruction, then 8 independent fma), order pinned; 4: those 128 fma alone.
+ * Timed by the caller; the times tell whether the two pipes overlap on this device.
+ *   out  DEVICE, at least CAOTE_ISSUE_PROBE_OUT_BYTES, written with values of no meaning.   */
+#define CAOTE_ISSUE_PROBE_VARIANTS 5
+#define CAOTE_ISSUE_PROBE_OUT_BYTES (256 * 512 * 4)
+caote_status caote_issue_probe(int32_t variant, int32_t iters, void* out, void* hip_stream);
+
 /* Text of the calling thread's most recent failure ("" if none).  The pointer
  * stays valid until that thread's next failing call.                               */
 const char* caote_last_error(void);

@@ -22,7 +22,7 @@ EXACT, FAST = 0, 1
 COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
 
 EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
-           "caote_append", "caote_evict", "caote_evict_static", "caote_evict_joint", "caote_evict_prefix", "caote_read_stream", "caote_phase_name", "caote_last_error",
+           "caote_append", "caote_evict", "caote_evict_static", "caote_evict_joint", "caote_evict_prefix", "caote_read_stream", "caote_issue_probe", "caote_phase_name", "caote_last_error",
            "caote_version")
 MAX_PHASES = 16
 JOINT_MAX_CAPACITY = 8192
@@ -86,6 +86,8 @@ def lib() -> ctypes.CDLL:
         L.caote_evict_prefix.restype = ctypes.c_int
         L.caote_read_stream.argtypes = [vp, sz, vp, vp]
         L.caote_read_stream.restype = ctypes.c_int
+        L.caote_issue_probe.argtypes = [i32, i32, vp, vp]
+        L.caote_issue_probe.restype = ctypes.c_int
         L.caote_phase_name.argtypes = [i32]
         L.caote_phase_name.restype = ctypes.c_char_p
         L.caote_last_error.argtypes = []
@@ -224,6 +226,15 @@ def caote_evict_prefix(q_window, K, V, base_score, layout: Layout, budget: int, 
 def caote_read_stream(buf, nbytes: int, sink, stream=None) -> None:
     """Measurement aid: one plain streaming read of `nbytes` at `buf`."""
     _check(lib().caote_read_stream(_ptr(buf), nbytes, _ptr(sink), _stream(stream)))
+
+
+ISSUE_PROBE_VARIANTS = ("mfma_16", "vector_block", "mfma_then_vector", "mfma_fma_interleaved", "fma_128")
+ISSUE_PROBE_OUT_BYTES = 256 * 512 * 4
+
+
+def caote_issue_probe(variant: int, iters: int, out, stream=None) -> None:
+    """Measurement aid: one launch of the issue-rate probe (see caote.h)."""
+    _check(lib().caote_issue_probe(variant, iters, _ptr(out), _stream(stream)))
 
 
 def layout_for(wl, cache_dev, row_lse=None) -> Layout:

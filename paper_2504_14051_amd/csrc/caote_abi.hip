@@ -461,6 +461,13 @@ caote_status caote_read_stream(const void* buf, size_t bytes, void* sink, void* 
   return device_status(caote::launch_read_stream(buf, bytes, sink, (hipStream_t)hip_stream), "read_stream");
 }
 
+caote_status caote_issue_probe(int32_t variant, int32_t iters, void* out, void* hip_stream) {
+  if (!out) return fail(CAOTE_EINVAL, "out must not be NULL");
+  if (variant < 0 || variant >= CAOTE_ISSUE_PROBE_VARIANTS) return fail(CAOTE_EINVAL, "unknown probe variant %d", variant);
+  if (iters < 1 || iters > (1 << 20)) return fail(CAOTE_EINVAL, "iters must be in [1, 2^20]");
+  return device_status(caote::launch_issue_probe(variant, iters, (float*)out, (hipStream_t)hip_stream), "issue_probe");
+}
+
 const char* caote_phase_name(int32_t i) {
   return i >= 0 && i < CAOTE_MAX_PHASES && g_phase_names[i] ? g_phase_names[i] : "";
 }

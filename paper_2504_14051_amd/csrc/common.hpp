@@ -218,6 +218,7 @@ hipError_t launch_select_joint(const Params& p, int32_t* order, float* err, int 
                                PhaseHook* hook);
 hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_read_stream(const void* buf, size_t bytes, void* sink, hipStream_t s);
+hipError_t launch_issue_probe(int variant, int iters, float* out, hipStream_t s);
 hipError_t launch_append(const Params& p, const void* k_new, const void* v_new, int n_at, int n_new,
                          hipStream_t s);
 

@@ -180,6 +180,16 @@ def test_read_stream_arguments_are_checked_on_the_host(B):
     B.caote_read_stream(fake, 0, fake, stream=0)                 # nothing to read: no launch
 
 
+def test_issue_probe_arguments_are_checked_on_the_host(B):
+    fake = 0x1000
+    for variant, iters, out in ((-1, 8, fake), (len(B.ISSUE_PROBE_VARIANTS), 8, fake), (0, 0, fake), (0, 8, None)):
+        with pytest.raises(B.CaoteError) as e:
+            B.caote_issue_probe(variant, iters, out, stream=0)
+        assert e.value.status == B.EINVAL
+    hdr = open(os.path.join(ROOT, "include", "caote.h")).read()
+    assert int(re.search(r"#define\s+CAOTE_ISSUE_PROBE_VARIANTS\s+(\d+)", hdr).group(1)) == len(B.ISSUE_PROBE_VARIANTS)
+
+
 def test_misaligned_data_pointers_are_rejected(B):
     """q, K and V are fetched in 16-byte pieces: a base address off that grid is refused on the
     host by every entry point that reads them."""

@@ -385,6 +385,7 @@ def joint_check(B, oracle, cache, budget, mode=0):
     _, oh, _ = H.oracle_scores(oracle, cache)
     V = cache.V.double().numpy()
     n_same = n_steps = 0
+    worst_margin = 0.0                  # largest (c[GPU's choice] - c[oracle's argmin]) / allowed slack seen
     for b, N in enumerate(H.lengths(cache)):
         lo = min(wl.n_protect_head, N)
         hi = max(lo, N - wl.n_protect_tail)
@@ -406,6 +407,8 @@ def joint_check(B, oracle, cache, budget, mode=0):
                 slack = 2 * rtol * (scale[s] + scale[j_best])
                 if np.isfinite(c[j_best]):
                     assert c[s] <= c[j_best] + slack, (b, hk, t, s, j_best, c[s], c[j_best])
+                    if slack > 0:
+                        worst_margin = max(worst_margin, float((c[s] - c[j_best]) / slack))
                     if rest_all - w[s] > 1e-3:
                         assert abs(jerr[b, hk, t] - c[s]) <= 2 * rtol * scale[s] + 1e-30, (b, hk, t)
                 n_same += s == j_best
@@ -418,6 +421,9 @@ def joint_check(B, oracle, cache, budget, mode=0):
     H.check_compaction(oracle, ref["K_before"], ref["V_before"], ref["base_before"], dev.K.cpu(), dev.V.cpu(),
                        None if base is None else base.cpu(), kept, cache, budget,
                        "swap_last" if mode == 1 else "stable")
+    # how much of the replay bound the run used: a regression shows here long before it fails
+    print(f"greedy replay: {n_same}/{n_steps} choices equal the oracle's argmin, "
+          f"worst excess over the argmin = {worst_margin:.3f} of the allowed slack")
     return n_same, n_steps
 
 
@@ -822,6 +828,16 @@ def test_read_stream_probe_runs_and_writes_nothing(B):
         B.caote_read_stream(buf, 24, sink)
     with pytest.raises(B.CaoteError):
         B.caote_read_stream(buf.data_ptr() + 8, 16, sink)
+
+
+def test_issue_probe_runs_every_variant(B):
+    """The measurement aid behind the benchmark's arithmetic floor: every variant launches and ends."""
+    out = torch.empty(B.ISSUE_PROBE_OUT_BYTES, dtype=torch.uint8, device="cuda")
+    for v in range(len(B.ISSUE_PROBE_VARIANTS)):
+        B.caote_issue_probe(v, 8, out)
+    torch.cuda.synchronize()
+    with pytest.raises(B.CaoteError):
+        B.caote_issue_probe(len(B.ISSUE_PROBE_VARIANTS), 8, out)
 
 
 def test_calls_in_flight_on_separate_streams_match_serial(B):
