@@ -112,12 +112,24 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   else
     p.split_len = chunk_len(1024, 256, 8192);
   p.n_split = ceil_div(p.cap, p.split_len);
+  // ragged lengths on the matrix-core path: equal shares of all heads' tiles per workgroup
+  // (common.hpp, Params::dyn_split); a share is never shorter than 1/32 of a full cache, so a
+  // head has at most 34 pieces
+  p.dyn_split = (p.use_mfma && p.seq_lens && p.B <= caote::kDynMaxBatch) ? 1 : 0;
+  if (p.dyn_split) {
+    p.dyn_wgs = p.R > 128 ? 256 : 512;
+    p.dyn_min_tiles = std::max(1, ceil_div(ceil_div(p.cap, 64), 32));
+    p.n_split = std::min(ceil_div(p.cap, 64), 34);
+    p.split_len = 64;      // (not used by the sweeps in this mode)
+  }
   p.split_len0 = p.split_len; p.n_split0 = p.n_split; p.n_rg0 = 1;
   if (p.use_mfma) {
     // rows a workgroup of the matrix-core sweeps keeps in registers (see launch_score_mfma)
     const int nrb = ceil_div(p.R, 32), rows = nrb <= 2 ? 64 : (nrb <= 4 ? 128 : 256);
     const int n_rg = ceil_div(p.R, rows);
-    if (n_rg > 1) {      // several row groups: side by side in the first sweep instead of in turn
+    if (n_rg > 1 && p.dyn_split) {
+      p.n_rg0 = n_rg;    // (each row group runs the same shares)
+    } else if (n_rg > 1) {      // several row groups: side by side in the first sweep instead of in turn
       const int want = std::max(1, (rows == 256 ? 256 : 512) / (BH * n_rg));
       p.split_len0 = std::max(128, (int)align_up((size_t)ceil_div(p.cap, want), 64));
       p.n_split0 = ceil_div(p.cap, p.split_len0);
@@ -149,6 +161,9 @@ size_t plan(const caote_layout* L, int32_t budget, Params& p, char* ws) {
   p.zpart = (float*)carve((size_t)BH * p.n_vpart * sizeof(float));
   p.osum = (float*)carve((size_t)BH * (caote::kMaxD + 1) * sizeof(float));
   p.hist = (uint32_t*)carve((size_t)BH * caote::kHistBins * sizeof(uint32_t));
+  p.seg_tab = (caote::SegTab*)carve(p.dyn_split ? (size_t)BH * sizeof(caote::SegTab) : 0);
+  p.wg_tab = (int32_t*)carve(p.dyn_split ? (size_t)p.dyn_wgs * sizeof(int32_t) : 0);
+  p.seg_glob = (int32_t*)carve(p.dyn_split ? 64 : 0);
   p.n_span = ceil_div(p.cap, caote::kSelSpan);
   p.sel_cand = (uint32_t*)carve((size_t)BH * p.cap * sizeof(uint32_t));
   p.sel_rec = (int32_t*)carve((size_t)BH * p.n_span * 2 * sizeof(int32_t));

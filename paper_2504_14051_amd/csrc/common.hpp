@@ -19,6 +19,8 @@ constexpr int kOneWgCap = 16384;  // largest cache whose selection one workgroup
 constexpr int kVSideSlots = 34;   // short caches: value rows a lane keeps in registers (k_vside)
 constexpr int kJointMaxCap = CAOTE_JOINT_MAX_CAPACITY;   // greedy joint eviction: weights of a head fit LDS
 
+struct SegTab { long long first; int tiles; int pad; };   // (see Params::seg_tab)
+
 // Everything a kernel needs to know about one call.  Passed by value.
 struct Params {
   const void* q;
@@ -64,6 +66,15 @@ struct Params {
   // the first key sweep and the merge of its row statistics: the same split unless the
   // matrix-core sweep has several row groups, which then go into the grid with longer splits
   int n_split0, split_len0, n_rg0;
+  // Ragged batches on the matrix-core path: the key tiles of all heads, laid end to end, are cut
+  // into equal shares, one per workgroup, wherever the cuts fall (a workgroup may finish one
+  // head and start the next); a head's pieces are its splits.  k_plan_splits fills the tables.
+  int dyn_split;      // the key sweeps take their splits from the tables below
+  int dyn_wgs;        // workgroups per sweep launch (shares)
+  int dyn_min_tiles;  // a share is at least this long, so that no head has more than n_split pieces
+  SegTab* seg_tab;    // [BH]       per head: index of its first tile in the end-to-end order, tiles
+  int32_t* wg_tab;    // [dyn_wgs]  per workgroup: the head its share starts in, -1: no work
+  int32_t* seg_glob;  // [0]        tiles per share
   int vrep, n_vsum;   // value sum: 256-token chunks per workgroup, partial sums per head
   int use_mfma;       // key sweeps on the matrix cores (bf16, head_dim 128, R > 16)
   int halo;           // SnapKV: pooling half-width (0 otherwise)
@@ -79,6 +90,29 @@ __device__ __forceinline__ int seq_len(const Params& p, int b) {
   if (p.seq_lens == nullptr) return p.cap;
   int n = p.seq_lens[b];
   return n < 0 ? 0 : (n > p.cap ? p.cap : n);
+}
+
+// Key splits of head bh on the matrix-core path: how many there are, and the keys [c0, c1) of
+// split s.  Equal lengths: cap cut into pieces of `split_len` keys.  Ragged batches: the pieces
+// that the workgroups' equal shares of the end-to-end tile sequence cut the head into.
+__device__ __forceinline__ int split_count(const Params& p, int bh, int N, int split_len) {
+  if (!p.dyn_split) return (N + split_len - 1) / split_len;
+  const SegTab t = p.seg_tab[bh];
+  if (t.tiles == 0) return 0;
+  const long long tpw = p.seg_glob[0];
+  return (int)((t.first + t.tiles - 1) / tpw - t.first / tpw) + 1;
+}
+__device__ __forceinline__ void split_range(const Params& p, int bh, int s, int N, int split_len, int& c0, int& c1) {
+  if (!p.dyn_split) {
+    c0 = s * split_len;
+    c1 = min(N, c0 + split_len);
+    return;
+  }
+  const SegTab t = p.seg_tab[bh];
+  const long long tpw = p.seg_glob[0], w = t.first / tpw + s;
+  const long long t0 = max(0ll, w * tpw - t.first), t1 = min((long long)t.tiles, (w + 1) * tpw - t.first);
+  c0 = (int)t0 * 64;
+  c1 = min(N, (int)t1 * 64);
 }
 
 // ---- 8-element row fragments ---------------------------------------------------
@@ -209,6 +243,7 @@ hipError_t launch_score_mfma(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_score_small(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook);
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook);
+constexpr int kDynMaxBatch = 1024;   // sequences the split planner handles in one workgroup
 hipError_t launch_value_passes(const Params& p, hipStream_t s, PhaseHook* hook);
 int vside_column_split(int cap);
 hipError_t launch_value_side(const Params& p, hipStream_t s, PhaseHook* hook);

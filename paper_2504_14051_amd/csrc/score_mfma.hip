@@ -68,25 +68,10 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   constexpr bool FUSE = MODE == 2;      // sweep 2 that also accumulates sum_j h_j v_j
   // Q reaches its registers through LDS (where one workgroup per compute unit leaves room)
   constexpr bool QLDS = NWV == 8;
-  const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
-  const int N = seq_len(p, b);
-  // the first sweep may have its own split, with the row groups spread over the grid
-  const int split_len = MODE == 0 ? p.split_len0 : p.split_len;
-  // Which split of the head this workgroup takes rotates with the head: workgroups go to the
-  // eight compute dies round-robin by their linear index, and with ragged lengths the splits
-  // near the start of a sequence are full while those near its end are short or empty, so a
-  // fixed blockIdx.x -> split mapping would hand some dies twice the work of others.
-  const int split = (int)((blockIdx.x + (unsigned)bh) % gridDim.x);
-  const int c0 = split * split_len;
-  // with the caller's normalisers this is the first kernel of the call: it clears the
-  // selection's counters (otherwise the merge of the row statistics does)
-  if (COLSUM && p.lse_in && blockIdx.x == 0) reset_counters(p, bh);
-  if (c0 >= N) return;
-  const int c1 = min(N, c0 + split_len);
-  const int ntiles = (c1 - c0 + kTN - 1) / kTN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / WK, kw = wave % WK;
-  const int P = p.wic ? N - p.W : N;    // keys below P are visible to every row
+  // the first sweep may have its own split, with the row groups spread over the grid
+  const int split_len = MODE == 0 ? p.split_len0 : p.split_len;
 
   __shared__ __attribute__((aligned(16))) unsigned char Ks[kNBuf][kTN * kRowBytes];
   __shared__ float a_lds[2][WR][kTN];
@@ -100,6 +85,51 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   __shared__ float hw[FUSE ? 4 * kTN : 1];
   __shared__ float bs[2][FUSE ? kTN : 1];
   __shared__ __attribute__((aligned(16))) unsigned char Vs[2][FUSE ? kTN * kRowBytes : 16];
+  __shared__ float red[NWV][kD + 4];    // FUSE: the waves' partial value sums
+
+  // ---- the pieces of work of this workgroup: (head, split, keys [c0, c1)) ------------------
+  // Equal lengths: one piece, from the block index.  Ragged batches: this workgroup's share of
+  // all heads' tiles laid end to end, which may end one head and start the next.
+  int dyn_bh = -1;
+  long long g = 0, g_end = 0, tpw = 1;
+  if (p.dyn_split) {
+    tpw = p.seg_glob[0];
+    dyn_bh = p.wg_tab[blockIdx.x];
+    g = (long long)blockIdx.x * tpw;
+    g_end = g + tpw;
+  }
+  for (bool first_piece = true;; first_piece = false) {
+  int bh, split, c0, c1_max;
+  if (!p.dyn_split) {
+    if (!first_piece) break;
+    bh = blockIdx.y;
+    // Which split of the head this workgroup takes rotates with the head: workgroups go to the
+    // eight compute dies round-robin by their linear index, and a fixed blockIdx.x -> split
+    // mapping would hand the dies unequal work when the splits near a sequence's end are short.
+    split = (int)((blockIdx.x + (unsigned)bh) % gridDim.x);
+    c0 = split * split_len;
+    c1_max = c0 + split_len;
+  } else {
+    if (dyn_bh < 0 || dyn_bh >= p.B * p.Hkv || g >= g_end) break;
+    const SegTab t = p.seg_tab[dyn_bh];
+    if (t.first >= g_end) break;
+    if (g >= t.first + t.tiles) { ++dyn_bh; continue; }     // past this head (or it is empty)
+    const long long t0 = max(g, t.first), t1 = min(g_end, t.first + t.tiles);
+    bh = dyn_bh;
+    split = (int)((long long)blockIdx.x - t.first / tpw);
+    c0 = (int)(t0 - t.first) * kTN;
+    c1_max = (int)(t1 - t.first) * kTN;
+    g = t1;
+  }
+  const int b = bh / p.Hkv, hk = bh % p.Hkv;
+  const int N = seq_len(p, b);
+  // with the caller's normalisers this is the first kernel of the call: it clears the
+  // selection's counters (otherwise the merge of the row statistics does)
+  if (COLSUM && p.lse_in && split == 0) reset_counters(p, bh);
+  if (c0 >= N) continue;
+  const int c1 = min(N, c1_max);
+  const int ntiles = (c1 - c0 + kTN - 1) / kTN;
+  const int P = p.wic ? N - p.W : N;    // keys below P are visible to every row
 
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(p.K) +
                             ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * 2;
@@ -457,7 +487,6 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
       }
 #pragma unroll
       for (int o = 32; o >= 1; o >>= 1) vz += __shfl_xor(vz, o, kWave);
-      __shared__ float red[NWV][kD + 4];
       if (lane < 16) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) red[wave][lane * 8 + e] = vacc[e];
@@ -502,6 +531,7 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
       }
     }
   }
+  }   // pieces of work
 }
 
 // lse2_r = log2 sum_j exp2(t_rj): one wave per query row, lanes stride over the splits.
@@ -513,7 +543,7 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_stats_wave(const Params
   const int lane = threadIdx.x & 63;
   if (r >= p.R) return;
   const int N = seq_len(p, b);
-  const int ns = (N + p.split_len0 - 1) / p.split_len0;
+  const int ns = split_count(p, bh, N, p.split_len0);
   const float* st = p.stats + ((int64_t)bh * p.n_split0 * p.Rp + r) * 2;
   float M = -INFINITY;
   for (int s = lane; s < ns; s += kWave) M = fmaxf(M, st[(int64_t)s * p.Rp * 2]);
@@ -688,11 +718,65 @@ hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook) {
 
 namespace {
 
+// Ragged batches: cuts the key tiles of all heads, laid end to end in (sequence, head) order,
+// into p.dyn_wgs equal shares and writes the tables the sweeps read (Params::seg_tab, wg_tab,
+// seg_glob).  One workgroup; the batch has at most kDynMaxBatch sequences.
+__global__ __launch_bounds__(kDynMaxBatch) void k_plan_splits(const Params p) {
+  __shared__ long long pre[kDynMaxBatch + 1];     // tiles of the sequences before b (one head each)
+  __shared__ int wave_tot[kDynMaxBatch / kWave];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int nt = tid < p.B ? (seq_len(p, tid) + kTN - 1) / kTN : 0;
+  int inc = nt;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) {
+    const int up = __shfl_up(inc, o, kWave);
+    if (lane >= o) inc += up;
+  }
+  if (lane == kWave - 1) wave_tot[wv] = inc;
+  __syncthreads();
+  long long before = 0;
+  for (int w = 0; w < wv; ++w) before += wave_tot[w];
+  pre[tid] = before + inc - nt;
+  if (tid == kDynMaxBatch - 1) pre[kDynMaxBatch] = before + inc;
+  __syncthreads();
+  const long long T = pre[kDynMaxBatch] * p.Hkv;          // (threads past the batch added nothing)
+  long long tpw = (T + p.dyn_wgs - 1) / p.dyn_wgs;
+  tpw = max(tpw, (long long)p.dyn_min_tiles);
+  if (tid == 0) p.seg_glob[0] = (int)tpw;
+  for (int bh = tid; bh < p.B * p.Hkv; bh += kDynMaxBatch) {
+    const int b = bh / p.Hkv, hk = bh % p.Hkv;
+    const int n = (int)(pre[b + 1] - pre[b]);
+    SegTab t;
+    t.first = pre[b] * p.Hkv + (long long)hk * n;
+    t.tiles = n;
+    t.pad = 0;
+    p.seg_tab[bh] = t;
+  }
+  for (int w = tid; w < p.dyn_wgs; w += kDynMaxBatch) {
+    const long long g0 = (long long)w * tpw;
+    int first = -1;
+    if (g0 < T) {
+      int lo = 0, hi = p.B;                 // the sequence b with pre[b] * Hkv <= g0 < pre[b+1] * Hkv
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (pre[mid] * p.Hkv <= g0) lo = mid; else hi = mid;
+      }
+      const long long n = pre[lo + 1] - pre[lo];
+      first = lo * p.Hkv + (int)((g0 - pre[lo] * p.Hkv) / n);
+    }
+    p.wg_tab[w] = first;
+  }
+}
+
 template <int NWV, int WR, int RBW>
 hipError_t launch_cfg(const Params& p, hipStream_t s, PhaseHook* hook) {
-  const dim3 grid(p.n_split, p.B * p.Hkv);
+  if (p.dyn_split) {
+    hipLaunchKernelGGL(k_plan_splits, dim3(1), dim3(kDynMaxBatch), 0, s, p);
+    if (mark(hook, "plan_splits")) return hipGetLastError();
+  }
+  const dim3 grid = p.dyn_split ? dim3(p.dyn_wgs) : dim3(p.n_split, p.B * p.Hkv);
   if (!p.lse_in) {                       // else the caller's attention pass has done sweep 1
-    const dim3 grid0(p.n_split0, p.B * p.Hkv, p.n_rg0);
+    const dim3 grid0 = p.dyn_split ? dim3(p.dyn_wgs, 1, p.n_rg0) : dim3(p.n_split0, p.B * p.Hkv, p.n_rg0);
     hipLaunchKernelGGL((k_logits_mfma<NWV, WR, RBW, 0>), grid0, dim3(NWV * kWave), 0, s, p);
     if (mark(hook, "key_rowstats")) return hipGetLastError();
     const hipError_t e = launch_merge_stats(p, s, hook);

@@ -166,8 +166,7 @@ __global__ __launch_bounds__(kThreads) void k_vsum(const Params p) {
 __global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
   const int bh = blockIdx.x, b = bh / p.Hkv, hk = bh % p.Hkv;
   const int N = seq_len(p, b);
-  const int part_len = p.fuse_v ? p.split_len : p.vrep * kVChunk;
-  const int nch = (N + part_len - 1) / part_len;
+  const int nch = p.fuse_v ? split_count(p, bh, N, p.split_len) : (N + p.vrep * kVChunk - 1) / (p.vrep * kVChunk);
   const int tid = threadIdx.x, D = p.D;
   // kFinalThreads / 128 groups x 128 columns; group g takes partials g, g+G, ...
   constexpr int G = kFinalThreads / kMaxD;
@@ -209,7 +208,8 @@ __global__ __launch_bounds__(kFinalThreads) void k_vfinal(const Params p) {
       for (int u = 0; u < kEdgeBatch; ++u) {
         const int idx = idx0 + u * kTeams;
         const int sp = idx / (2 * halo), o = idx - sp * 2 * halo;
-        const int c0 = sp * p.split_len, c1 = min(N, c0 + p.split_len);
+        int c0, c1;
+        split_range(p, bh, sp, N, p.split_len, c0, c1);
         const int j = o < halo ? c0 + o : c1 - 2 * halo + o;
         // front edge: the first `halo` tokens of the split; back edge: the last `halo`, unless
         // the split is so short that the front edge already covers them
