@@ -128,6 +128,9 @@ def main():
                     help="second figure: the same steps with this many calls (different layers) in flight "
                          "on streams of their own; 1 leaves it out")
     ap.add_argument("--no-issue-probe", action="store_true")
+    ap.add_argument("--no-batched-layers", action="store_true",
+                    help="decode workload: leave out the all-layers-as-one-call figure (under a kernel trace "
+                         "its batch-512 launches would be averaged into the per-layer kernels' durations)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (each (sequence, layer, KV head) is "
@@ -549,6 +552,7 @@ def main():
             "cached_tokens_per_s": wl.batch * wl.context * n_layers / (step_ms * 1e-3),
             "note": f"{n_layers} layers with independent caches, one call per layer in the model's order, "
                     f"inside one HIP graph; a generation step appends one token to each of {wl.batch} sequences"}
+    if decode_stream and not args.no_graph and not args.no_batched_layers:
         Kb = torch.cat([K for (_, K, _, _) in layers], dim=0)
         Vb = torch.cat([V for (_, _, V, _) in layers], dim=0)
         qb = torch.cat([q for (q, _, _, _) in layers], dim=0)
