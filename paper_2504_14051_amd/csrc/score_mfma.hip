@@ -559,6 +559,27 @@ __global__ __launch_bounds__(kMergeThreads) void k_merge_stats_wave(const Params
   if (lane == 0) p.lse2[(int64_t)bh * p.Rp + r] = L > 0.f ? M + log2f(L) : INFINITY;
 }
 
+// The same merge with one thread per query row: consecutive threads read consecutive rows of a
+// split's statistics, so a batch of many heads moves whole cache lines.
+__global__ __launch_bounds__(kMergeThreads) void k_merge_stats_rows(const Params p) {
+  const int bh = blockIdx.y, b = bh / p.Hkv;
+  if (blockIdx.x == 0) reset_counters(p, bh);
+  const int r = blockIdx.x * kMergeThreads + threadIdx.x;
+  if (r >= p.R) return;
+  const int N = seq_len(p, b);
+  const int ns = split_count(p, bh, N, p.split_len0);
+  const float2* st = reinterpret_cast<const float2*>(p.stats) + (int64_t)bh * p.n_split0 * p.Rp + r;
+  float M = -INFINITY;
+#pragma unroll 8
+  for (int s = 0; s < ns; ++s) M = fmaxf(M, st[(int64_t)s * p.Rp].x);
+  float L = 0.f;
+#pragma unroll 8
+  for (int s = 0; s < ns; ++s) {
+    const float2 ml = st[(int64_t)s * p.Rp];
+    if (ml.x > -INFINITY) L += ml.y * exp2f(ml.x - M);
+  }
+  p.lse2[(int64_t)bh * p.Rp + r] = L > 0.f ? M + log2f(L) : INFINITY;
+}
 
 // ---------------------------------------------------------------------------------------
 // Few query rows (R <= 8: decode-time eviction, Sec. 2 generation) on the matrix cores.
@@ -711,7 +732,13 @@ hipError_t launch_score_few_mfma(const Params& p, hipStream_t s, PhaseHook* hook
 
 
 hipError_t launch_merge_stats(const Params& p, hipStream_t s, PhaseHook* hook) {
-  hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kMergeThreads), 0, s, p);
+  // few rows in all: a wave per row keeps the launch short; many (batches): a thread per row,
+  // whose loads coalesce over the rows
+  if ((long long)p.B * p.Hkv * p.R >= 16384)
+    hipLaunchKernelGGL(k_merge_stats_rows, dim3((p.R + kMergeThreads - 1) / kMergeThreads, p.B * p.Hkv),
+                       dim3(kMergeThreads), 0, s, p);
+  else
+    hipLaunchKernelGGL(k_merge_stats_wave, dim3((p.R + 3) / 4, p.B * p.Hkv), dim3(kMergeThreads), 0, s, p);
   if (mark(hook, "merge_stats")) return hipGetLastError();
   return hipGetLastError();
 }
