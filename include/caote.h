@@ -248,10 +248,14 @@ caote_status caote_read_stream(const void* buf, size_t bytes, void* sink, void* 
  * issues per 64-key tile, on registers only, 256 workgroups of eight waves (as the sweeps
  * run).  variant 0: the 16 matrix instructions alone; 1: the vector work alone (32 logits per
  * lane: scale, exp2, maximum, sum); 2: both, the vector work on the matrix results; 3: 16 x
- * (one matrix instruction, then 8 independent fma), order pinned; 4: those 128 fma alone.
+ * (one matrix instruction, then 8 independent fma), order pinned; 4: those 128 fma alone;
+ * 5-7: the work of variant 2 in workgroup-barrier intervals of one kind each (every wave issues
+ * the matrix instructions of two tiles in one interval and the vector work on their results in
+ * the next): 5 with waves 0-3 and 4-7 taking the two kinds in opposite order, 7 with even and
+ * odd waves doing so, 6 with all waves in the same order.
  * Timed by the caller; the times tell whether the two pipes overlap on this device.
  *   out  DEVICE, at least CAOTE_ISSUE_PROBE_OUT_BYTES, written with values of no meaning.   */
-#define CAOTE_ISSUE_PROBE_VARIANTS 5
+#define CAOTE_ISSUE_PROBE_VARIANTS 8
 #define CAOTE_ISSUE_PROBE_OUT_BYTES (256 * 512 * 4)
 caote_status caote_issue_probe(int32_t variant, int32_t iters, void* out, void* hip_stream);
 

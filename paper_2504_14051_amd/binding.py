@@ -228,7 +228,8 @@ def caote_read_stream(buf, nbytes: int, sink, stream=None) -> None:
     _check(lib().caote_read_stream(_ptr(buf), nbytes, _ptr(sink), _stream(stream)))
 
 
-ISSUE_PROBE_VARIANTS = ("mfma_16", "vector_block", "mfma_then_vector", "mfma_fma_interleaved", "fma_128")
+ISSUE_PROBE_VARIANTS = ("mfma_16", "vector_block", "mfma_then_vector", "mfma_fma_interleaved", "fma_128",
+                        "intervals_opposite_halves", "intervals_same_order", "intervals_opposite_parity")
 ISSUE_PROBE_OUT_BYTES = 256 * 512 * 4
 
 
