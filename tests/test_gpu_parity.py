@@ -297,6 +297,17 @@ def test_small_shapes_ragged(B, oracle, kw):
     full_check(B, oracle, cache, wl.budget)
 
 
+@pytest.mark.parametrize("ragged", [False, True], ids=["dense", "ragged"])
+def test_many_heads_short_caches(B, oracle, ragged):
+    """12 sequences x 8 KV heads x 256 query rows on caches of a few hundred tokens: the row
+    statistics are merged with one thread per row (batches of many heads), the splits are a
+    tile or two long, and in the ragged case a workgroup's share of tiles spans several heads."""
+    wl = small(batch=12, n_q_heads=32, n_kv_heads=8, window=64, context=520, budget=130,
+               base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=64)
+    lens = np.array([520, 64, 519, 130, 321, 65, 520, 448, 131, 200, 64, 385], dtype=np.int32) if ragged else None
+    full_check(B, oracle, synth.make_cache(wl, seq_lens=lens), wl.budget)
+
+
 @pytest.mark.parametrize("kw", [
     dict(window=64),                                   # R = 256: eight-wave matrix-core sweep
     dict(window=32, base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=32),   # R = 128
