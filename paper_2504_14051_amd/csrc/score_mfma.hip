@@ -68,7 +68,10 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
   constexpr bool FUSE = MODE == 2;      // sweep 2 that also accumulates sum_j h_j v_j
   // Q reaches its registers through LDS (where one workgroup per compute unit leaves room)
   constexpr bool QLDS = NWV == 8;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // the wave index as a scalar: everything derived from it (ring addresses, row blocks) then
+  // stays on the scalar unit
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave / WK, kw = wave % WK;
   // the first sweep may have its own split, with the row groups spread over the grid
   const int split_len = MODE == 0 ? p.split_len0 : p.split_len;
@@ -143,14 +146,30 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
     // a wave fills the 16-byte slot base + 16 L), kNBuf-1 tiles ahead of the math.  The
     // XOR swizzle that keeps the fragment reads conflict-free is applied on the global
     // side: the lane that owns slot (row, pc) fetches chunk pc ^ (row & 15) of that row.
-    auto issue = [&](int t, int buf) {
+    // this lane's piece of tile 0, per load: tiles that lie inside the cache are then one
+    // 64-bit add away (the tile stride is a scalar); only the last tile clamps its rows
+    const unsigned char* kp0[LPT];
 #pragma unroll
-      for (int u = 0; u < LPT; ++u) {
-        const int slot = (wave * LPT + u) * kWave + lane;    // 16-byte slot inside the tile
-        const int row = slot / kChunks, pc = slot % kChunks;
-        const int j = min(c0 + t * kTN + row, N - 1);        // rows past the end repeat the last one
-        load_to_lds16(Kb + j * krow + ((pc ^ (row & 15)) << 4),
-                      __builtin_amdgcn_readfirstlane(lds_addr(&Ks[buf][(wave * LPT + u) * kWave * 16])));
+    for (int u = 0; u < LPT; ++u) {
+      const int slot = (wave * LPT + u) * kWave + lane;      // 16-byte slot inside the tile
+      const int row = slot / kChunks, pc = slot % kChunks;
+      kp0[u] = Kb + (int64_t)(c0 + row) * krow + ((pc ^ (row & 15)) << 4);
+    }
+    const int64_t ktile = (int64_t)kTN * krow;
+    auto issue = [&](int t, int buf) {
+      const uint32_t dst = lds_addr(&Ks[0][0]) + (uint32_t)(buf * kTN * kRowBytes + wave * LPT * kWave * 16);
+      if (c0 + (t + 1) * kTN <= N) {
+        const int64_t off = (int64_t)t * ktile;
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) load_to_lds16(kp0[u] + off, dst + u * kWave * 16);
+      } else {
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) {
+          const int slot = (wave * LPT + u) * kWave + lane;
+          const int row = slot / kChunks, pc = slot % kChunks;
+          const int j = min(c0 + t * kTN + row, N - 1);      // rows past the end repeat the last one
+          load_to_lds16(Kb + j * krow + ((pc ^ (row & 15)) << 4), dst + u * kWave * 16);
+        }
       }
     };
     // The first two K tiles are requested before anything else, so that their latency
@@ -384,19 +403,23 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
     const int64_t vrow = p.vsn * 2;
     const int jrow = c0 - halo + wave * RW + (lane >> 4);    // this lane's row of step 0, u = 0
     const unsigned char* vlane = Vb + (int64_t)jrow * vrow + ((lane & 15) << 4);
-    auto v_issue = [&](int s, unsigned char* vs) {
-      const int j0 = jrow + s * kTN;
-      if (j0 - (lane >> 4) >= 0 && j0 - (lane >> 4) + RW <= N) {   // wave-uniform: no clamping
-        const unsigned char* ps = vlane + (int64_t)(s * kTN) * vrow;
+    const unsigned char* vp0[LPT];
 #pragma unroll
-        for (int u = 0; u < LPT; ++u)
-          load_to_lds16(ps + u * 4 * vrow, __builtin_amdgcn_readfirstlane(lds_addr(vs + (wave * LPT + u) * kWave * 16)));
+    for (int u = 0; u < LPT; ++u) vp0[u] = vlane + (int64_t)(u * 4) * vrow;
+    const int64_t vtile = (int64_t)kTN * vrow;
+    auto v_issue = [&](int s, unsigned char* vs) {
+      const int jw0 = c0 - halo + wave * RW + s * kTN;        // the wave's first row of step s
+      const uint32_t dst = lds_addr(vs) + (uint32_t)(wave * LPT * kWave * 16);
+      if (jw0 >= 0 && jw0 + RW <= N) {                        // wave-uniform: no clamping
+        const int64_t off = (int64_t)s * vtile;
+#pragma unroll
+        for (int u = 0; u < LPT; ++u) load_to_lds16(vp0[u] + off, dst + u * kWave * 16);
       } else {
+        const int j0 = jrow + s * kTN;
 #pragma unroll
         for (int u = 0; u < LPT; ++u) {
           const int j = min(max(j0 + u * 4, 0), N - 1);
-          load_to_lds16(Vb + j * vrow + ((lane & 15) << 4),
-                        __builtin_amdgcn_readfirstlane(lds_addr(vs + (wave * LPT + u) * kWave * 16)));
+          load_to_lds16(Vb + j * vrow + ((lane & 15) << 4), dst + u * kWave * 16);
         }
       }
     };
