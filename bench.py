@@ -413,12 +413,12 @@ def main():
     # outputs); the narrow kernels of one call (merges, selection, compaction) then share the
     # chip with the wide sweeps of another.  `value` stays the one-call-at-a-time figure, the one
     # the per-kernel durations and the committed profiles belong to.
-    dt_two = None
+    dt_two = dt_two_lse = None
     NL = max(1, min(args.calls_in_flight, n_layers))
     if not args.no_graph and NL >= 2:
         lanes_res = [(ws, scores, kept)] + [(torch.empty_like(ws), torch.empty_like(scores), torch.empty_like(kept)) for _ in range(NL - 1)]
 
-        def two_lanes(lo, hi, main):
+        def two_lanes(lo, hi, main, with_lse=False):
             sts = [main] + [torch.cuda.Stream() for _ in range(NL - 1)]
             for st in sts[1:]:
                 st.wait_stream(main)
@@ -429,7 +429,8 @@ def main():
                 if blockwise:
                     k_new, v_new = blocks[i % n_layers]
                     B.caote_append(K, V, base, k_new, v_new, L, wl.budget, wl.window, st)
-                B.caote_evict(q, K, V, base, L, wl.budget, mode, sc, kp, w, st)
+                B.caote_evict(q, K, V, base, lse_layouts[i % n_layers][1] if with_lse else L, wl.budget, mode,
+                              sc, kp, w, st)
             for st in sts[1:]:
                 main.wait_stream(st)
 
@@ -447,6 +448,19 @@ def main():
             g_two.replay()
             torch.cuda.synchronize()
             dt_two = time.perf_counter() - t0
+            # ... and with the caller's row normalisers handed over as well: the configuration a
+            # serving loop that owns the attention pass would run
+            two_lanes(0, 4, side, with_lse=True)
+            side.synchronize()
+            g_two_lse = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_two_lse, stream=side):
+                two_lanes(args.warmup, args.warmup + args.steps, side, with_lse=True)
+            g_two_lse.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            g_two_lse.replay()
+            torch.cuda.synchronize()
+            dt_two_lse = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = wl.batch * wl.context / (dt / args.steps)
 
@@ -564,6 +578,11 @@ def main():
             "value": wl.batch * wl.context / (dt_two / args.steps), "unit": "tokens/s",
             "note": "the same K steps, step i (layer i mod layers) on stream i mod n: independent "
                     "calls overlap, total time / K"}
+        if dt_two_lse is not None:
+            out["calls_in_flight"]["given_row_lse"] = {
+                "ms_per_step": dt_two_lse / args.steps * 1e3,
+                "value": wl.batch * wl.context / (dt_two_lse / args.steps), "unit": "tokens/s",
+                "note": "the same with layout.row_lse set: no first key sweep"}
     # What bounds a key sweep's arithmetic on this device: the per-tile instruction mix on
     # registers only, matrix and vector work alone and together (caote_issue_probe).
     if use_probe:
