@@ -70,6 +70,8 @@ def lib():
         L.oracle_compact_stable.restype = i
         L.oracle_compact_swap_last.argtypes = [_bp, i, sz, _ip, i]
         L.oracle_compact_swap_last.restype = i
+        L.oracle_compact_fill.argtypes = [_bp, i, sz, _ip, i]
+        L.oracle_compact_fill.restype = i
         L.oracle_bruteforce_eviction_error.argtypes = [_dp, _dp, i, i, _dp]
         L.oracle_bruteforce_eviction_error.restype = None
         L.oracle_bruteforce_delete_token.argtypes = [_dp, _dp, _dp, i, i, dbl, _dp]
@@ -204,7 +206,8 @@ def compact_one(rows, idx, mode="stable"):
     N = rows.shape[0]
     row_bytes = rows.nbytes // max(N, 1)
     idx = np.ascontiguousarray(idx, dtype=np.int32)
-    fn = lib().oracle_compact_stable if mode == "stable" else lib().oracle_compact_swap_last
+    fn = {"stable": lib().oracle_compact_stable, "swap_last": lib().oracle_compact_swap_last,
+          "fill": lib().oracle_compact_fill}[mode]
     n = fn(rows.ctypes.data_as(_bp), N, row_bytes, idx.ctypes.data_as(_ip), idx.shape[0])
     if n < 0:
         raise ValueError("oracle compact: swap_last needs exactly one evicted token")

@@ -319,8 +319,8 @@ void oracle_select(const double *c, int N, int budget, int32_t *idx)
  *   stable    : out row i = in row idx[i], i < n_keep  (ascending order kept)
  *   swap_last : exactly one token is evicted (n_keep = N-1); the evicted
  *               position receives the last row, everything else stays put.
- * Both work in place on `rows` ([N][row_bytes]); rows beyond the new length
- * are left untouched.  Returns the new length.
+ * All work in place on `rows` ([N][row_bytes]); rows beyond the new length
+ * are left untouched.  Return the new length.
  * ------------------------------------------------------------------------- */
 int oracle_compact_stable(unsigned char *rows, int N, size_t row_bytes,
                           const int32_t *idx, int budget)
@@ -348,6 +348,31 @@ int oracle_compact_swap_last(unsigned char *rows, int N, size_t row_bytes,
     if (jstar != N - 1)
         memcpy(rows + (size_t)jstar * row_bytes, rows + (size_t)(N - 1) * row_bytes, row_bytes);
     return N - 1;
+}
+
+/* fill : the kept rows that already lie below the new length n_keep stay where
+ * they are; the kept rows from at or beyond n_keep move, in ascending order,
+ * into the positions below n_keep that evicted rows leave free, taken in
+ * ascending order as well (there are as many of the one as of the other).  The
+ * kept SET is what Sec. 2 fixes; the order of the rows is the caller's choice,
+ * and this one moves the fewest rows.  With one evicted token it is swap_last. */
+int oracle_compact_fill(unsigned char *rows, int N, size_t row_bytes,
+                        const int32_t *idx, int budget)
+{
+    int n_keep = 0;
+    while (n_keep < budget && idx[n_keep] >= 0) ++n_keep;
+    if (n_keep >= N) return N;            /* nothing evicted */
+    unsigned char *is_kept = (unsigned char *)calloc((size_t)N, 1);
+    for (int i = 0; i < n_keep; ++i) is_kept[idx[i]] = 1;
+    int src = n_keep;                     /* next kept row at or beyond n_keep */
+    for (int x = 0; x < n_keep; ++x) {
+        if (is_kept[x]) continue;         /* stays where it is */
+        while (!is_kept[src]) ++src;
+        memcpy(rows + (size_t)x * row_bytes, rows + (size_t)src * row_bytes, row_bytes);
+        ++src;
+    }
+    free(is_kept);
+    return n_keep;
 }
 
 /* ------------------------------------------------------------------------- *

@@ -446,6 +446,47 @@ def test_compact_stable_and_swap_last(oracle):
     np.testing.assert_array_equal(out, rows)
 
 
+def test_compact_fill_moves_only_rows_from_beyond_the_new_length(oracle):
+    """Hole-filling compaction against its statement written with numpy set operations: kept rows
+    below the new length stay, the kept rows from beyond it drop into the freed positions, both in
+    ascending order.  Special cases that reduce to the other two modes."""
+    for seed, (n, n_keep) in enumerate([(12, 6), (40, 13), (40, 39), (40, 1), (300, 150), (300, 20), (64, 32)]):
+        rng = np.random.default_rng(4100 + seed)
+        rows = rng.integers(0, 2 ** 31, size=(n, 3)).astype(np.uint32)
+        idx = np.sort(rng.choice(n, size=n_keep, replace=False)).astype(np.int32)
+        out, m = oracle.compact_one(rows, idx, "fill")
+        assert m == n_keep
+        holes = np.array(sorted(set(range(n_keep)) - set(idx.tolist())), dtype=np.int64)
+        movers = idx[idx >= n_keep]
+        assert len(holes) == len(movers)
+        ref = rows.copy()
+        ref[holes] = rows[movers]
+        np.testing.assert_array_equal(out, ref)              # rows at and beyond n_keep untouched too
+        stay = idx[idx < n_keep]
+        np.testing.assert_array_equal(out[stay], rows[stay])
+        # the rows below the new length are exactly the kept rows, each once
+        assert sorted(map(tuple, out[:n_keep])) == sorted(map(tuple, rows[idx]))
+    n = 12
+    rows = RNG.integers(0, 2 ** 15, size=(n, 5)).astype(np.uint16)
+    for jstar in (0, 5, n - 1):                              # one evicted token: swap_last
+        idx = np.delete(np.arange(n, dtype=np.int32), jstar)
+        a, _ = oracle.compact_one(rows, idx, "fill")
+        b, _ = oracle.compact_one(rows, idx, "swap_last")
+        np.testing.assert_array_equal(a, b)
+    idx = np.arange(6, 12, dtype=np.int32)                   # every kept row from beyond: stable
+    a, _ = oracle.compact_one(rows, idx, "fill")
+    b, _ = oracle.compact_one(rows, idx, "stable")
+    np.testing.assert_array_equal(a, b)
+    idx = np.arange(6, dtype=np.int32)                       # the first rows kept: nothing moves
+    a, m = oracle.compact_one(rows, idx, "fill")
+    assert m == 6
+    np.testing.assert_array_equal(a, rows)
+    idx = np.concatenate([np.arange(n), [-1, -1]]).astype(np.int32)   # nothing evicted
+    a, m = oracle.compact_one(rows, idx, "fill")
+    assert m == n
+    np.testing.assert_array_equal(a, rows)
+
+
 # ---- the batched wrapper only loops ----------------------------------------------
 
 def test_batched_wrapper_matches_single_instances(oracle):
