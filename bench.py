@@ -338,6 +338,20 @@ def main():
                 "note": "variant = CAOTE_FAST; Spearman rank correlation of FastCAOTE and CAOTE scores per "
                         "(sequence, KV head) over the scored tokens of layer 0"}
 
+    # The same step with the hole-filling compaction (CAOTE_COMPACT_FILL: kept rows below the new
+    # length stay, the others drop into the freed positions; one kernel, fewest rows moved).
+    fill = None
+    if not args.no_graph and mode == B.COMPACT_STABLE and wl.budget <= B.FILL_MAX_BUDGET:
+        def step_fill(i):
+            q, K, V, base = layers[i % n_layers]
+            append(i)
+            B.caote_evict(q, K, V, base, L, wl.budget, B.COMPACT_FILL, scores, kept, ws, stream)
+        dt_fill = timed_replay(step_fill, n_again=2)
+        fill = {"ms_per_step": dt_fill / args.steps * 1e3, "ms_per_step_replays": replays.pop(),
+                "value": wl.batch * wl.context / (dt_fill / args.steps), "unit": "tokens/s",
+                "note": "mode = CAOTE_COMPACT_FILL instead of CAOTE_COMPACT_STABLE: same kept set, rows not in "
+                        "ascending order afterwards"}
+
     # Every timed step above works on a cache that earlier steps have already compacted (the
     # layer buffers rotate and are not restored).  The same call on caches that no call has
     # touched: one buffer per step, all restored from pristine copies before every replay.
@@ -606,6 +620,8 @@ def main():
         out["fastcaote"] = fast
     if fresh is not None:
         out["fresh_caches"] = fresh
+    if fill is not None:
+        out["fill_compaction"] = fill
     if dt_joint is not None:
         out["joint_selection"] = {
             "ms_per_step": dt_joint / args.steps * 1e3,

@@ -73,10 +73,22 @@ typedef enum {
 } caote_variant;
 
 typedef enum {
-  CAOTE_COMPACT_STABLE = 0,   /* row i <- row kept_idx[i]; ascending order preserved */
-  CAOTE_COMPACT_SWAP_LAST = 1 /* exactly one token evicted: the last row moves into
-                                 the hole, all other rows stay where they are        */
+  CAOTE_COMPACT_STABLE = 0,    /* row i <- row kept_idx[i]; ascending order preserved */
+  CAOTE_COMPACT_SWAP_LAST = 1, /* exactly one token evicted: the last row moves into
+                                  the hole, all other rows stay where they are; a
+                                  sequence that evicts any other number of tokens is
+                                  compacted as in CAOTE_COMPACT_STABLE                */
+  CAOTE_COMPACT_FILL = 2       /* the fewest row moves for any number of evictions:
+                                  kept rows below the new length n = min(N_b, budget)
+                                  stay where they are, the kept rows at or beyond n go,
+                                  in ascending order, into the positions below n that
+                                  evicted rows leave free, taken in ascending order.
+                                  Sec. 2 fixes the kept SET, not the order of the rows
+                                  (keys carry their positions); kept_idx still lists
+                                  the kept tokens in ascending order, not by new row.
+                                  budget <= CAOTE_FILL_MAX_BUDGET.                     */
 } caote_compact_mode;
+#define CAOTE_FILL_MAX_BUDGET 16384
 
 typedef struct caote_layout {
   int32_t batch, n_q_heads, n_kv_heads, head_dim; /* head_dim in {64, 128}           */

@@ -19,7 +19,8 @@ OK, EINVAL, EUNSUPPORTED, EWORKSPACE, EDEVICE = 0, -1, -2, -3, -4
 BF16, F32 = 0, 1
 BASE_NONE, BASE_H2O, BASE_SNAPKV = 0, 1, 2
 EXACT, FAST = 0, 1
-COMPACT_STABLE, COMPACT_SWAP_LAST = 0, 1
+COMPACT_STABLE, COMPACT_SWAP_LAST, COMPACT_FILL = 0, 1, 2
+FILL_MAX_BUDGET = 16384
 
 EXPORTS = ("caote_workspace_bytes", "caote_score", "caote_select", "caote_compact",
            "caote_append", "caote_evict", "caote_evict_static", "caote_evict_joint", "caote_evict_prefix", "caote_read_stream", "caote_issue_probe", "caote_phase_name", "caote_last_error",

@@ -311,6 +311,14 @@ caote_status caote_select(const float* scores, const caote_layout* layout, int32
   return device_status(caote::launch_select(p, (hipStream_t)hip_stream, nullptr), "select");
 }
 
+static caote_status check_mode(int32_t mode, int32_t budget) {
+  if (mode != CAOTE_COMPACT_STABLE && mode != CAOTE_COMPACT_SWAP_LAST && mode != CAOTE_COMPACT_FILL)
+    return fail(CAOTE_EINVAL, "unknown compaction mode %d", mode);
+  if (mode == CAOTE_COMPACT_FILL && budget > CAOTE_FILL_MAX_BUDGET)
+    return fail(CAOTE_EUNSUPPORTED, "CAOTE_COMPACT_FILL takes budgets up to %d (got %d)", CAOTE_FILL_MAX_BUDGET, budget);
+  return CAOTE_OK;
+}
+
 caote_status caote_compact(void* K, void* V, float* base_score, const int32_t* kept_idx,
                            const caote_layout* layout, int32_t budget, int32_t mode,
                            void* workspace, size_t workspace_bytes, void* hip_stream) {
@@ -318,8 +326,7 @@ caote_status caote_compact(void* K, void* V, float* base_score, const int32_t* k
   if (st != CAOTE_OK) return st;
   if (!K || !V || !kept_idx) return fail(CAOTE_EINVAL, "K, V and kept_idx must not be NULL");
   if ((st = check_aligned16(nullptr, K, V)) != CAOTE_OK) return st;
-  if (mode != CAOTE_COMPACT_STABLE && mode != CAOTE_COMPACT_SWAP_LAST)
-    return fail(CAOTE_EINVAL, "unknown compaction mode %d", mode);
+  if ((st = check_mode(mode, budget)) != CAOTE_OK) return st;
   Params p;
   st = check_ws(layout, budget, workspace, workspace_bytes, p);
   if (st != CAOTE_OK) return st;
@@ -372,8 +379,7 @@ static caote_status check_evict_args(const void* q_window, const void* K, const 
   if ((st = check_aligned16(q_window, K, V)) != CAOTE_OK) return st;
   if (layout->base == CAOTE_BASE_H2O && !base_score)
     return fail(CAOTE_EINVAL, "CAOTE_BASE_H2O needs base_score (the accumulator)");
-  if (mode != CAOTE_COMPACT_STABLE && mode != CAOTE_COMPACT_SWAP_LAST)
-    return fail(CAOTE_EINVAL, "unknown compaction mode %d", mode);
+  if ((st = check_mode(mode, budget)) != CAOTE_OK) return st;
   return CAOTE_OK;
 }
 

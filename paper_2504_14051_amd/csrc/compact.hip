@@ -12,6 +12,7 @@
 //
 // Evict-one sequences in SWAP_LAST mode move a single row (k_swap_last): the last row drops
 // into the hole.  A sequence that evicts any other number of tokens is compacted stably.
+// FILL mode generalises the swap to any number of evictions (k_fill_holes).
 #include "common.hpp"
 
 namespace caote {
@@ -115,6 +116,74 @@ __global__ __launch_bounds__(kThreads) void k_move_rows(const Params p, int row_
   }
 }
 
+// CAOTE_COMPACT_FILL: the kept rows below the new length stay, the kept rows from at or beyond
+// it ("movers", ascending) drop into the positions below it that evicted rows leave free
+// ("holes", ascending).  Sources and destinations are disjoint, so one kernel and no staging.
+// The kept list is ascending: its first p entries are the rows that stay, and the q-th hole is
+// q + #{i < p : idx[i] - i <= q} (idx[i] - i = holes below idx[i], non-decreasing in i).
+// A workgroup takes kFillRows movers; the list of the rows that stay sits in LDS for the
+// searches (p <= budget <= CAOTE_FILL_MAX_BUDGET entries).
+constexpr int kFillRows = 64;
+
+__global__ __launch_bounds__(kThreads) void k_fill_holes(const Params p, int row_bytes) {
+  const int bh = blockIdx.y, b = bh / p.Hkv, hk = bh % p.Hkv;
+  const int N = seq_len(p, b);
+  const int n_keep = min(N, p.budget);
+  if (N <= n_keep) return;                             // nothing evicted
+  const int q0 = blockIdx.x * kFillRows;
+  if (q0 >= N - n_keep) return;                        // at most N - n_keep rows can move
+  const int32_t* idx = p.kept + (int64_t)bh * p.budget;
+  __shared__ int s_seg, s_p;
+  __shared__ int s_dst[kFillRows], s_src[kFillRows];
+  __shared__ int s_idx[CAOTE_FILL_MAX_BUDGET];
+  const int tid = threadIdx.x;
+  // p = first rank whose index is >= n_keep: the segment first (one probe per thread), then
+  // the rank inside it
+  if (tid == 0) { s_seg = kThreads; s_p = n_keep; }
+  __syncthreads();
+  const int seg = (n_keep + kThreads - 1) / kThreads;
+  {
+    const int e = min(n_keep, (tid + 1) * seg) - 1;
+    if (tid * seg < n_keep && idx[e] >= n_keep) atomicMin(&s_seg, tid);
+  }
+  __syncthreads();
+  if (s_seg < kThreads) {
+    const int i0 = s_seg * seg, i1 = min(n_keep, i0 + seg);
+    for (int i = i0 + tid; i < i1; i += kThreads)
+      if (idx[i] >= n_keep) atomicMin(&s_p, i);
+  }
+  __syncthreads();
+  const int np = s_p, m = n_keep - np;                 // rows that stay, rows that move
+  if (q0 >= m) return;
+  for (int i = tid; i < np; i += kThreads) s_idx[i] = idx[i];
+  const int rows = min(kFillRows, m - q0);
+  if (tid < rows) s_src[tid] = idx[np + q0 + tid];
+  __syncthreads();
+  if (tid < rows) {
+    const int q = q0 + tid;
+    int lo = 0, hi = np;                               // count of i with s_idx[i] - i <= q
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (s_idx[mid] - mid <= q) lo = mid + 1; else hi = mid;
+    }
+    s_dst[tid] = q + lo;
+  }
+  __syncthreads();
+  const int esz = p.dtype == CAOTE_F32 ? 4 : 2;
+  char* Kb = reinterpret_cast<char*>(p.K) + ((int64_t)b * p.ksb + (int64_t)hk * p.ksh) * esz;
+  char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
+  const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
+  const int cpr = row_bytes / 16;
+  for (int id = tid; id < rows * cpr; id += kThreads) {
+    const int r = id / cpr, ch = id % cpr;
+    const int src = s_src[r], dst = s_dst[r];
+    if (src < n_keep || src >= N || dst >= n_keep) continue;   // (a malformed list moves nothing out of bounds)
+    *reinterpret_cast<uint4*>(Kb + dst * krow + ch * 16) = *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
+    *reinterpret_cast<uint4*>(Vb + dst * vrow + ch * 16) = *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
+    if (ch == 0 && p.base) p.base[(int64_t)bh * p.cap + dst] = p.base[(int64_t)bh * p.cap + src];
+  }
+}
+
 // Block-wise prefill (Sec. 2): the new block's rows go behind the rows a sequence holds.
 // One thread per 16-byte chunk of a new row; K and V in the same pass.
 __global__ __launch_bounds__(kThreads) void k_append(const Params p, const char* k_new, const char* v_new,
@@ -153,6 +222,15 @@ hipError_t launch_compact(const Params& p, hipStream_t s, PhaseHook* hook) {
   const int row_bytes = p.D * (p.dtype == CAOTE_F32 ? 4 : 2);
   const int64_t chunks = (int64_t)p.budget * (row_bytes / 16);
   const dim3 grid((unsigned)((chunks + kThreads - 1) / kThreads), p.B * p.Hkv);
+  if (p.mode == CAOTE_COMPACT_FILL) {
+    // movers per (sequence, head): at most min(budget, cap - budget)
+    const int most = p.budget < p.cap - p.budget ? p.budget : p.cap - p.budget;
+    if (most <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_holes, dim3((most + kFillRows - 1) / kFillRows, p.B * p.Hkv), dim3(kThreads), 0, s, p,
+                       row_bytes);
+    if (mark(hook, "compact_fill")) return hipGetLastError();
+    return hipGetLastError();
+  }
   if (p.mode == CAOTE_COMPACT_SWAP_LAST) {
     if (!p.select_swaps) {               // else the selection kernel has moved the row already
       hipLaunchKernelGGL(k_swap_last, dim3(p.B * p.Hkv), dim3(kThreads), 0, s, p, row_bytes);

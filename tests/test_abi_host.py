@@ -104,6 +104,15 @@ def test_null_pointers_budget_mode_and_workspace_errors(B):
     with pytest.raises(B.CaoteError) as e:                       # bad mode
         B.caote_compact(fake, fake, None, fake, L, 64, 7, ws, stream=0, workspace_bytes=need)
     assert e.value.status == B.EINVAL
+    big = good_layout(B, capacity=40000)                         # hole-filling mode: budget limit
+    with pytest.raises(B.CaoteError) as e:
+        B.caote_compact(fake, fake, None, fake, big, B.FILL_MAX_BUDGET + 1, B.COMPACT_FILL, ws, stream=0,
+                        workspace_bytes=B.caote_workspace_bytes(big, B.FILL_MAX_BUDGET + 1))
+    assert e.value.status == B.EUNSUPPORTED and "CAOTE_COMPACT_FILL" in str(e.value)
+    with pytest.raises(B.CaoteError) as e:
+        B.caote_evict(fake, fake, fake, fake, big, B.FILL_MAX_BUDGET + 1, B.COMPACT_FILL, fake, fake, ws, stream=0,
+                      workspace_bytes=B.caote_workspace_bytes(big, B.FILL_MAX_BUDGET + 1))
+    assert e.value.status == B.EUNSUPPORTED
     with pytest.raises(B.CaoteError) as e:                       # workspace too small
         B.caote_select(fake, L, 64, fake, ws, stream=0, workspace_bytes=need - 1)
     assert e.value.status == B.EWORKSPACE and "needed" in str(e.value)

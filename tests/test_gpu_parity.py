@@ -66,7 +66,7 @@ def full_check(B, oracle, cache, budget, mode=0, variant=0, row_lse=None):
                                        rtol=rtol, atol=1e-7)
     H.check_compaction(oracle, res["K_before"], res["V_before"], res["base_before"],
                        res["K_after"], res["V_after"], res["base_after"], res["kept"], cache,
-                       budget, "swap_last" if mode == 1 else "stable")
+                       budget, ("stable", "swap_last", "fill")[mode])
     # rows past each sequence's length are never written
     for b, N in enumerate(H.lengths(cache)):
         assert np.isnan(res["scores"][b, :, N:]).all()
@@ -431,7 +431,7 @@ def joint_check(B, oracle, cache, budget, mode=0):
             assert np.array_equal(kept[b, hk, :n_keep], want) and (kept[b, hk, n_keep:] == -1).all()
     H.check_compaction(oracle, ref["K_before"], ref["V_before"], ref["base_before"], dev.K.cpu(), dev.V.cpu(),
                        None if base is None else base.cpu(), kept, cache, budget,
-                       "swap_last" if mode == 1 else "stable")
+                       ("stable", "swap_last", "fill")[mode])
     # how much of the replay bound the run used: a regression shows here long before it fails
     print(f"greedy replay: {n_same}/{n_steps} choices equal the oracle's argmin, "
           f"worst excess over the argmin = {worst_margin:.3f} of the allowed slack")
@@ -650,7 +650,8 @@ def test_select_exact_with_ties_and_infinities(B, oracle, cap, budget):
 
 @pytest.mark.parametrize("pattern", ["identity", "tail", "every_other", "head_then_tail", "shift_one"])
 @pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 128), (torch.float32, 64), (torch.bfloat16, 64)])
-def test_compact_hazard_patterns(B, oracle, pattern, dtype, d):
+@pytest.mark.parametrize("cmode", ["stable", "fill"])
+def test_compact_hazard_patterns(B, oracle, pattern, dtype, d, cmode):
     cap, budget = 3000, 1400
     idx = {
         "identity": np.arange(budget),
@@ -669,10 +670,41 @@ def test_compact_hazard_patterns(B, oracle, pattern, dtype, d):
     L = B.make_layout(torch.empty(1, 2, 1, d, dtype=dtype, device="cuda"), dK, dV, base=B.BASE_NONE,
                       softmax_scale=1.0)
     ws = torch.empty(B.caote_workspace_bytes(L, budget), dtype=torch.uint8, device="cuda")
-    B.caote_compact(dK, dV, db, kept.cuda(), L, budget, B.COMPACT_STABLE, ws)
+    B.caote_compact(dK, dV, db, kept.cuda(), L, budget, B.COMPACT_FILL if cmode == "fill" else B.COMPACT_STABLE, ws)
     torch.cuda.synchronize()
     cache = synth.Cache(None, None, K, V, base, None)
-    H.check_compaction(oracle, K, V, base, dK.cpu(), dV.cpu(), db.cpu(), kept.numpy(), cache, budget)
+    H.check_compaction(oracle, K, V, base, dK.cpu(), dV.cpu(), db.cpu(), kept.numpy(), cache, budget, cmode)
+    if cmode == "fill":          # rows at and beyond the new length are sources only: untouched
+        assert torch.equal(dK.cpu()[:, :, budget:], K[:, :, budget:]) and torch.equal(dV.cpu()[:, :, budget:], V[:, :, budget:])
+
+
+@pytest.mark.parametrize("kw,budget", [
+    (dict(), 200),                                                      # H2O accumulator moves along
+    (dict(base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=8), 650),    # few evictions
+    (dict(window=64, context=5000), 1),                                 # budget 1
+    (dict(window=64, context=5000, base=synth.BASE_SNAPKV, pool_kernel=7, n_protect_tail=64), 2048),
+    (dict(window=1, n_q_heads=2, n_kv_heads=2, context=2049), 2048),    # evict one: the swap
+    (dict(dtype="f32", head_dim=64), 300),
+    (dict(context=20000, window=32), 16384),                            # the largest budget the mode takes
+], ids=lambda x: "-".join(f"{k}={v}" for k, v in x.items()) if isinstance(x, dict) else str(x))
+def test_fill_compaction_mode(B, oracle, kw, budget):
+    """CAOTE_COMPACT_FILL through all three entry points (score/select/compact and the fused call):
+    kept rows below the new length stay, the others fill the freed positions (ragged batch)."""
+    wl = small(**kw)
+    lens = np.array([wl.context, max(wl.window + 1, wl.context // 3)], dtype=np.int32)
+    cache = synth.make_cache(wl, seq_lens=lens, base_init="random")
+    full_check(B, oracle, cache, budget, mode=2)
+
+
+def test_fill_compaction_rejects_larger_budgets(B):
+    wl = small(context=40000, window=32, budget=B.FILL_MAX_BUDGET + 1)
+    c = synth.make_cache(wl)
+    q, K, V = c.q.cuda(), c.K.cuda(), c.V.cuda()
+    L = B.make_layout(q, K, V, base=wl.base, softmax_scale=wl.softmax_scale, window_in_cache=wl.window_in_cache)
+    ws = torch.empty(B.caote_workspace_bytes(L, wl.budget), dtype=torch.uint8, device="cuda")
+    kept = torch.zeros(*K.shape[:2], wl.budget, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.CaoteError):
+        B.caote_compact(K, V, None, kept, L, wl.budget, B.COMPACT_FILL, ws)
 
 
 @pytest.mark.parametrize("cap", [2, 257, 5000, 20000])
