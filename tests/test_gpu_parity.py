@@ -463,6 +463,13 @@ def test_greedy_joint_eviction_prefill_block(B, oracle):
     joint_check(B, oracle, cache, wl.budget)
 
 
+def test_greedy_joint_eviction_with_fill_compaction(B, oracle):
+    """The joint selection followed by the hole-filling compaction (ragged batch, 40 tokens leave)."""
+    wl = small(context=600, window=8)
+    cache = synth.make_cache(wl, seq_lens=np.array([600, 575], dtype=np.int32), base_init="random")
+    joint_check(B, oracle, cache, 560, mode=2)
+
+
 def test_greedy_joint_eviction_limits(B):
     wl = small(context=CAP_JOINT + 64, window=8)
     dev = H.to_device(synth.make_cache(wl))
