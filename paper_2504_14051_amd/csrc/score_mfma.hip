@@ -180,18 +180,25 @@ __global__ __launch_bounds__(NWV * kWave, 2) void k_logits_mfma(const Params p) 
       // DMA into LDS (16 lanes per row, swizzled), fragments by ds_read_b128.  Loading the
       // fragments straight from global memory (32 rows x 32 bytes per instruction) keeps
       // the address unit busy for several microseconds per workgroup.
+      // A load instruction of a wave covers four consecutive rows, its next one the four after
+      // them: the lane's address is worked out once and then stepped (window position + 4, with
+      // the carry into the next query head), the multiplications stay out of the loop.
+      constexpr int kQLoads = ROWS * kChunks / kThreads;
+      const int row0 = wave * kQLoads * (kWave / kChunks) + lane / kChunks, pc = lane % kChunks;
+      int qg, qiw;
+      divmod_w(p, rg0 + row0, qg, qiw);
+      const unsigned char* qp = reinterpret_cast<const unsigned char*>(p.q) +
+          ((int64_t)b * p.qsb + (int64_t)(hk * p.G + qg) * p.qsh + (int64_t)qiw * p.qsw) * 2;
+      const int64_t q_step = (int64_t)(kWave / kChunks) * p.qsw * 2, q_carry = (p.qsh - (int64_t)p.W * p.qsw) * 2;
+      const uint32_t q_dst = lds_addr(&Qs[0]) + (uint32_t)(wave * kQLoads * kWave * 16);
 #pragma unroll 1
-      for (int u = 0; u < ROWS * kChunks / kThreads; ++u) {
-        const int slot = (wave * (ROWS * kChunks / kThreads) + u) * kWave + lane;
-        const int row = slot / kChunks, pc = slot % kChunks;
-        if (rg0 + row < p.R) {            // rows past R are not fetched; their fragments are zeroed
-          int g, iw;
-          divmod_w(p, rg0 + row, g, iw);
-          const unsigned char* qp = reinterpret_cast<const unsigned char*>(p.q) +
-              ((int64_t)b * p.qsb + (int64_t)(hk * p.G + g) * p.qsh + (int64_t)iw * p.qsw) * 2;
-          load_to_lds16(qp + ((pc ^ (row & 15)) << 4),
-                        __builtin_amdgcn_readfirstlane(lds_addr(&Qs[(slot - lane) * 16])));
-        }
+      for (int u = 0; u < kQLoads; ++u) {
+        const int row = row0 + u * (kWave / kChunks);
+        if (rg0 + row < p.R)              // rows past R are not fetched; their fragments are zeroed
+          load_to_lds16(qp + ((pc ^ (row & 15)) << 4), q_dst + u * kWave * 16);
+        qp += q_step;
+        qiw += kWave / kChunks;
+        while (qiw >= p.W) { qiw -= p.W; qp += q_carry; }
       }
     }
     for (int t = 0; t < kNBuf - 1 && t < ntiles; ++t) issue(t, t);
