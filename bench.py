@@ -586,6 +586,8 @@ def main():
                               "bytes_per_step": kv_bytes,
                               "note": "plain streaming read of the same K and V buffers, same rotation: "
                                       "the rate no sweep over them can exceed on this device"}
+        out["path"]["frac_of_read_stream"] = out["path"]["achieved"] / out["read_stream"]["achieved"]
+        out["roofline"]["frac_of_read_stream"] = out["roofline"]["achieved"] / out["read_stream"]["achieved"]
     if dt_two is not None:
         out["calls_in_flight"] = {
             "n": NL, "ms_per_step": dt_two / args.steps * 1e3,
