@@ -121,8 +121,8 @@ __global__ __launch_bounds__(kThreads) void k_move_rows(const Params p, int row_
 // ("holes", ascending).  Sources and destinations are disjoint, so one kernel and no staging.
 // The kept list is ascending: its first p entries are the rows that stay, and the q-th hole is
 // q + #{i < p : idx[i] - i <= q} (idx[i] - i = holes below idx[i], non-decreasing in i).
-// A workgroup takes kFillRows movers; the list of the rows that stay sits in LDS for the
-// searches (p <= budget <= CAOTE_FILL_MAX_BUDGET entries).
+// A workgroup takes kFillRows movers; the kept list sits in LDS for the count and the searches
+// (budget <= CAOTE_FILL_MAX_BUDGET entries).
 constexpr int kFillRows = 64;
 
 __global__ __launch_bounds__(kThreads) void k_fill_holes(const Params p, int row_bytes) {
@@ -133,32 +133,27 @@ __global__ __launch_bounds__(kThreads) void k_fill_holes(const Params p, int row
   const int q0 = blockIdx.x * kFillRows;
   if (q0 >= N - n_keep) return;                        // at most N - n_keep rows can move
   const int32_t* idx = p.kept + (int64_t)bh * p.budget;
-  __shared__ int s_seg, s_p;
-  __shared__ int s_dst[kFillRows], s_src[kFillRows];
+  __shared__ int s_p;
+  __shared__ int s_dst[kFillRows];
   __shared__ int s_idx[CAOTE_FILL_MAX_BUDGET];
   const int tid = threadIdx.x;
-  // p = first rank whose index is >= n_keep: the segment first (one probe per thread), then
-  // the rank inside it
-  if (tid == 0) { s_seg = kThreads; s_p = n_keep; }
+  // The whole kept list comes into LDS in one round of loads; p = number of its entries below
+  // n_keep (it is ascending, so they are its first p).
+  if (tid == 0) s_p = 0;
   __syncthreads();
-  const int seg = (n_keep + kThreads - 1) / kThreads;
-  {
-    const int e = min(n_keep, (tid + 1) * seg) - 1;
-    if (tid * seg < n_keep && idx[e] >= n_keep) atomicMin(&s_seg, tid);
+  int below = 0;
+  for (int i = tid; i < n_keep; i += kThreads) {
+    const int v = idx[i];
+    s_idx[i] = v;
+    below += v < n_keep ? 1 : 0;
   }
-  __syncthreads();
-  if (s_seg < kThreads) {
-    const int i0 = s_seg * seg, i1 = min(n_keep, i0 + seg);
-    for (int i = i0 + tid; i < i1; i += kThreads)
-      if (idx[i] >= n_keep) atomicMin(&s_p, i);
-  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) below += __shfl_xor(below, o, kWave);
+  if ((tid & (kWave - 1)) == 0 && below) atomicAdd(&s_p, below);
   __syncthreads();
   const int np = s_p, m = n_keep - np;                 // rows that stay, rows that move
   if (q0 >= m) return;
-  for (int i = tid; i < np; i += kThreads) s_idx[i] = idx[i];
   const int rows = min(kFillRows, m - q0);
-  if (tid < rows) s_src[tid] = idx[np + q0 + tid];
-  __syncthreads();
   if (tid < rows) {
     const int q = q0 + tid;
     int lo = 0, hi = np;                               // count of i with s_idx[i] - i <= q
@@ -176,7 +171,7 @@ __global__ __launch_bounds__(kThreads) void k_fill_holes(const Params p, int row
   const int cpr = row_bytes / 16;
   for (int id = tid; id < rows * cpr; id += kThreads) {
     const int r = id / cpr, ch = id % cpr;
-    const int src = s_src[r], dst = s_dst[r];
+    const int src = s_idx[np + q0 + r], dst = s_dst[r];
     if (src < n_keep || src >= N || dst >= n_keep) continue;   // (a malformed list moves nothing out of bounds)
     *reinterpret_cast<uint4*>(Kb + dst * krow + ch * 16) = *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
     *reinterpret_cast<uint4*>(Vb + dst * vrow + ch * 16) = *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
