@@ -134,7 +134,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (each (sequence, layer, KV head) is "
-              "independent; see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+              "independent, so sharding by any of them needs no exchange). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch
