@@ -169,13 +169,35 @@ __global__ __launch_bounds__(kThreads) void k_fill_holes(const Params p, int row
   char* Vb = reinterpret_cast<char*>(p.V) + ((int64_t)b * p.vsb + (int64_t)hk * p.vsh) * esz;
   const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
   const int cpr = row_bytes / 16;
-  for (int id = tid; id < rows * cpr; id += kThreads) {
-    const int r = id / cpr, ch = id % cpr;
-    const int src = s_idx[np + q0 + r], dst = s_dst[r];
-    if (src < n_keep || src >= N || dst >= n_keep) continue;   // (a malformed list moves nothing out of bounds)
-    *reinterpret_cast<uint4*>(Kb + dst * krow + ch * 16) = *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
-    *reinterpret_cast<uint4*>(Vb + dst * vrow + ch * 16) = *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
-    if (ch == 0 && p.base) p.base[(int64_t)bh * p.cap + dst] = p.base[(int64_t)bh * p.cap + src];
+  // four chunks per thread at a time, all their loads requested before the first store (the
+  // compiler cannot know that sources and destinations are different rows)
+  constexpr int kB = 4;
+  for (int id0 = tid; id0 < rows * cpr; id0 += kB * kThreads) {
+    uint4 kk[kB], vv[kB];
+    float bb[kB];
+    int dd[kB], cc[kB];
+#pragma unroll
+    for (int u = 0; u < kB; ++u) {
+      const int id = id0 + u * kThreads;
+      dd[u] = -1;
+      if (id < rows * cpr) {
+        const int r = id / cpr, ch = id % cpr;
+        const int src = s_idx[np + q0 + r], dst = s_dst[r];
+        if (src >= n_keep && src < N && dst < n_keep) {          // (a malformed list moves nothing out of bounds)
+          dd[u] = dst; cc[u] = ch;
+          kk[u] = *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
+          vv[u] = *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
+          bb[u] = ch == 0 && p.base ? p.base[(int64_t)bh * p.cap + src] : 0.f;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kB; ++u) {
+      if (dd[u] < 0) continue;
+      *reinterpret_cast<uint4*>(Kb + dd[u] * krow + cc[u] * 16) = kk[u];
+      *reinterpret_cast<uint4*>(Vb + dd[u] * vrow + cc[u] * 16) = vv[u];
+      if (cc[u] == 0 && p.base) p.base[(int64_t)bh * p.cap + dd[u]] = bb[u];
+    }
   }
 }
 
