@@ -97,22 +97,29 @@ __global__ __launch_bounds__(kThreads) void k_move_rows(const Params p, int row_
                                         2 * (int64_t)p.B * p.Hkv * p.budget * row_bytes) +
                (int64_t)bh * p.budget;
   const int64_t krow = p.ksn * esz, vrow = p.vsn * esz;
+  // (both loads, and the accumulator's, before the first store: one round trip, not two)
+  const bool acc = ch == 0 && p.base;
   if (DIR == 0) {
-    *reinterpret_cast<uint4*>(stK + (int64_t)i * row_bytes + ch * 16) =
-        *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
-    *reinterpret_cast<uint4*>(stV + (int64_t)i * row_bytes + ch * 16) =
-        *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
-    if (ch == 0 && p.base) stB[i] = p.base[(int64_t)bh * p.cap + src];
+    const uint4 k4 = *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
+    const uint4 v4 = *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
+    const float b1 = acc ? p.base[(int64_t)bh * p.cap + src] : 0.f;
+    *reinterpret_cast<uint4*>(stK + (int64_t)i * row_bytes + ch * 16) = k4;
+    *reinterpret_cast<uint4*>(stV + (int64_t)i * row_bytes + ch * 16) = v4;
+    if (acc) stB[i] = b1;
   } else if (direct) {
-    *reinterpret_cast<uint4*>(Kb + i * krow + ch * 16) = *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
-    *reinterpret_cast<uint4*>(Vb + i * vrow + ch * 16) = *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
-    if (ch == 0 && p.base) p.base[(int64_t)bh * p.cap + i] = p.base[(int64_t)bh * p.cap + src];
+    const uint4 k4 = *reinterpret_cast<const uint4*>(Kb + src * krow + ch * 16);
+    const uint4 v4 = *reinterpret_cast<const uint4*>(Vb + src * vrow + ch * 16);
+    const float b1 = acc ? p.base[(int64_t)bh * p.cap + src] : 0.f;
+    *reinterpret_cast<uint4*>(Kb + i * krow + ch * 16) = k4;
+    *reinterpret_cast<uint4*>(Vb + i * vrow + ch * 16) = v4;
+    if (acc) p.base[(int64_t)bh * p.cap + i] = b1;
   } else {
-    *reinterpret_cast<uint4*>(Kb + i * krow + ch * 16) =
-        *reinterpret_cast<const uint4*>(stK + (int64_t)i * row_bytes + ch * 16);
-    *reinterpret_cast<uint4*>(Vb + i * vrow + ch * 16) =
-        *reinterpret_cast<const uint4*>(stV + (int64_t)i * row_bytes + ch * 16);
-    if (ch == 0 && p.base) p.base[(int64_t)bh * p.cap + i] = stB[i];
+    const uint4 k4 = *reinterpret_cast<const uint4*>(stK + (int64_t)i * row_bytes + ch * 16);
+    const uint4 v4 = *reinterpret_cast<const uint4*>(stV + (int64_t)i * row_bytes + ch * 16);
+    const float b1 = acc ? stB[i] : 0.f;
+    *reinterpret_cast<uint4*>(Kb + i * krow + ch * 16) = k4;
+    *reinterpret_cast<uint4*>(Vb + i * vrow + ch * 16) = v4;
+    if (acc) p.base[(int64_t)bh * p.cap + i] = b1;
   }
 }
 
