@@ -114,7 +114,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=200,
+                    help="untimed steps before the timed ones; when equal to --steps they are a first replay of "
+                         "the timed graph itself (its one-time upload then falls into the warm-up)")
     ap.add_argument("--workload", default="llama3-8b-32k")
     ap.add_argument("--layers", type=int, default=0,
                     help="independent layer buffers to rotate over (default 16; 32 for the decode stream: its model's depth)")
@@ -257,13 +259,16 @@ def main():
                 step_fn(i)
             side.synchronize()
             g_warm, g_timed = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g_warm, stream=side):
-                for i in range(args.warmup):
-                    step_fn(i)
+            if args.warmup and args.warmup != args.steps:
+                with torch.cuda.graph(g_warm, stream=side):
+                    for i in range(args.warmup):
+                        step_fn(i)
             with torch.cuda.graph(g_timed, stream=side):
                 for i in range(args.steps):
                     step_fn(args.warmup + i)
-            if args.warmup:
+            if args.warmup == args.steps:
+                g_timed.replay()         # W = K: the warm-up steps are a first replay of the same graph
+            elif args.warmup:
                 g_warm.replay()
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -655,13 +660,14 @@ def main():
         wsb = torch.empty(B.caote_workspace_bytes(Lb, wl.budget), dtype=torch.uint8, device="cuda")
         sb = torch.empty(Kb.shape[:3], device="cuda")
         kb = torch.empty((*Kb.shape[:2], wl.budget), dtype=torch.int32, device="cuda")
-        saved_steps = args.steps
+        saved_steps, saved_warm = args.steps, args.warmup
         args.steps = max(4, min(args.steps // n_layers, 20))
+        args.warmup = args.steps
         dt_b = timed_replay(lambda i: B.caote_evict(qb, Kb, Vb, bb, Lb, wl.budget, mode, sb, kb, wsb, stream))
         out["decode_stream"]["all_layers_one_call"] = {
             "ms_per_generation_step": dt_b / args.steps * 1e3, "steps": args.steps,
             "note": f"the same step as one call over {Kb.shape[0]} sequences (all layers batched)"}
-        args.steps = saved_steps
+        args.steps, args.warmup = saved_steps, saved_warm
         del Kb, Vb, qb, bb, wsb, sb, kb
     if decode_stream and args.ragged_prefill:
         pw = synth.llama3_8b_32k().with_(batch=wl.batch, name="llama3-8b-prefill-ragged16")
@@ -674,7 +680,7 @@ def main():
         ps = torch.empty(pK.shape[:3], device="cuda")
         pk = torch.empty((*pK.shape[:2], pw.budget), dtype=torch.int32, device="cuda")
         saved_steps, saved_warm = args.steps, args.warmup
-        args.steps, args.warmup = 10, 2
+        args.steps, args.warmup = 10, 10
         dt_p = timed_replay(lambda i: B.caote_evict(pq, pK, pV, None, pL, pw.budget, B.COMPACT_STABLE, ps, pk, pws, stream))
         out["ragged_prefill_eviction"] = {
             "tokens": int(lens.sum()), "sequences": pw.batch, "ms_per_call": dt_p / args.steps * 1e3,
