@@ -640,7 +640,8 @@ def main():
     # The decode stream as the workload states it: one generation step is one evict-one call per
     # layer, 32 layers with caches of their own, each layer's call after the one before (the
     # model's own order).  Two more figures: the 32 calls of a step as ONE call over 32 x 16
-    # sequences (no dependency between layers: an upper bound), and, on request, the ragged
+    # sequences (the evictions of a step do not depend on each other, so they can be deferred to the
+    # end of the token's forward pass and issued together), and, on request, the ragged
     # prefill eviction that brings the 16 prompts down to the budget.
     if decode_stream and not args.no_graph:
         step_ms = ms_per_step * n_layers
@@ -666,7 +667,8 @@ def main():
         dt_b = timed_replay(lambda i: B.caote_evict(qb, Kb, Vb, bb, Lb, wl.budget, mode, sb, kb, wsb, stream))
         out["decode_stream"]["all_layers_one_call"] = {
             "ms_per_generation_step": dt_b / args.steps * 1e3, "steps": args.steps,
-            "note": f"the same step as one call over {Kb.shape[0]} sequences (all layers batched)"}
+            "note": f"the same step as one call over {Kb.shape[0]} sequences (all layers batched: the evictions of a "
+                    f"generation step deferred to the end of the forward pass)"}
         args.steps, args.warmup = saved_steps, saved_warm
         del Kb, Vb, qb, bb, wsb, sb, kb
     if decode_stream and args.ragged_prefill:
