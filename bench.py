@@ -130,6 +130,8 @@ def main():
                     help="second figure: the same steps with this many calls (different layers) in flight "
                          "on streams of their own; 1 leaves it out")
     ap.add_argument("--no-issue-probe", action="store_true")
+    ap.add_argument("--layers-per-call", type=int, default=8,
+                    help="layers_one_call figure: this many layers' caches as the batch of one call")
     ap.add_argument("--no-batched-layers", action="store_true",
                     help="decode workload: leave out the all-layers-as-one-call figure (under a kernel trace "
                          "its batch-512 launches would be averaged into the per-layer kernels' durations)")
@@ -483,6 +485,58 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = wl.batch * wl.context / (dt / args.steps)
 
+    # The other way to have several layers in flight: ONE call over several layers' caches (the
+    # batch dimension; layers allocated at a constant stride, e.g. all layers of a prompt evicted
+    # together after its prefill).  --layers-per-call layers per call, from copies of the rotating buffers.
+    stacked = None
+    if not args.no_graph and not blockwise and not decode_stream and n_layers >= 4 and wl.batch == 1 \
+            and 2 * K0.numel() * K0.element_size() * n_layers <= (24 << 30):
+        LPC = max(2, min(args.layers_per_call, n_layers))
+        groups = []
+        for g0 in range(0, n_layers - LPC + 1, LPC):
+            grp = layers[g0:g0 + LPC]
+            groups.append((torch.cat([x[0] for x in grp]), torch.cat([x[1] for x in grp]),
+                           torch.cat([x[2] for x in grp]),
+                           torch.cat([x[3] for x in grp]) if wl.base == synth.BASE_H2O else None))
+        gq, gK, gV, _ = groups[0]
+        Lg = B.make_layout(gq, gK, gV, base=wl.base, softmax_scale=wl.softmax_scale,
+                           window_in_cache=wl.window_in_cache, pool_kernel=wl.pool_kernel,
+                           n_protect_head=wl.n_protect_head, n_protect_tail=wl.n_protect_tail)
+        wsg = torch.empty(B.caote_workspace_bytes(Lg, wl.budget), dtype=torch.uint8, device="cuda")
+        scg = torch.empty(LPC, wl.n_kv_heads, wl.context, device="cuda")
+        kpg = torch.empty(LPC, wl.n_kv_heads, wl.budget, dtype=torch.int32, device="cuda")
+
+        def step_stacked(i):
+            q, K, V, base = groups[i % len(groups)]
+            B.caote_evict(q, K, V, base, Lg, wl.budget, mode, scg, kpg, wsg, stream)
+        saved_steps, saved_warm = args.steps, args.warmup
+        args.steps = max(4, args.steps // LPC)
+        args.warmup = args.steps
+        dt_g = timed_replay(step_stacked)
+        stacked = {"layers_per_call": LPC, "ms_per_layer": dt_g / args.steps / LPC * 1e3,
+                   "value": LPC * wl.context / (dt_g / args.steps), "unit": "tokens/s",
+                   "note": f"one caote_evict call over {LPC} layers' caches (batch = {LPC}): the narrow kernels are "
+                           f"paid once per call"}
+        # ... and with the caller's row normalisers
+        if lse_layouts:
+            g_lse = []
+            for gi, g0 in enumerate(range(0, n_layers - LPC + 1, LPC)):
+                lse_g = torch.cat([lse_layouts[g0 + i][0] for i in range(LPC)])
+                q, K, V, _ = groups[gi]
+                g_lse.append((lse_g, B.make_layout(
+                    q, K, V, base=wl.base, softmax_scale=wl.softmax_scale, window_in_cache=wl.window_in_cache,
+                    pool_kernel=wl.pool_kernel, n_protect_head=wl.n_protect_head,
+                    n_protect_tail=wl.n_protect_tail, row_lse=lse_g)))
+
+            def step_stacked_lse(i):
+                q, K, V, base = groups[i % len(groups)]
+                B.caote_evict(q, K, V, base, g_lse[i % len(groups)][1], wl.budget, mode, scg, kpg, wsg, stream)
+            dt_gl = timed_replay(step_stacked_lse)
+            stacked["given_row_lse"] = {"ms_per_layer": dt_gl / args.steps / LPC * 1e3,
+                                        "value": LPC * wl.context / (dt_gl / args.steps), "unit": "tokens/s"}
+        args.steps, args.warmup = saved_steps, saved_warm
+        del groups, wsg, scg, kpg
+
     # Per-kernel durations: the call cut after its k-th kernel, for every k, each as a graph of
     # the same steps over the same rotation of buffers; kernel k costs T(k) - T(k-1).
     q, K, V, base = layers[0]
@@ -625,6 +679,8 @@ def main():
                     "fully) and their sum (not at all): the arithmetic floor of a key sweep's tile"}
     if fast is not None:
         out["fastcaote"] = fast
+    if stacked is not None:
+        out["layers_one_call"] = stacked
     if fresh is not None:
         out["fresh_caches"] = fresh
     if fill is not None:
