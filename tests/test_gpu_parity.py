@@ -119,6 +119,14 @@ def test_llama3_8b_32k_snapkv_given_row_normalisers(B, oracle):
     full_check(B, oracle, cache, wl.budget, row_lse=lse)
 
 
+@pytest.mark.parametrize("wl_fn,batch", [(synth.llama3_8b_32k, 8), (synth.llama3_8b_4k, 8)], ids=["32k", "4k"])
+def test_eight_layers_as_one_call(B, oracle, wl_fn, batch):
+    """The launch configuration of the benchmark's `layers_one_call` figure: eight caches of the
+    named layer as the batch of one call (64 heads: longer key splits than the one-layer call)."""
+    wl = wl_fn().with_(batch=batch)
+    full_check(B, oracle, synth.make_cache(wl), wl.budget)
+
+
 def test_qwen25_7b_128k_snapkv(B, oracle):
     wl = synth.qwen25_7b_128k()
     full_check(B, oracle, synth.make_cache(wl), wl.budget)
